@@ -1,0 +1,106 @@
+/*
+ * attnw.h -- C ABI of libattnw: attention weights on AMD MI355X (gfx950).
+ *
+ *     P = softmax(scale * Q K^T)      row-wise over keys, for every (batch, head)
+ *
+ * The operation is the one the paper narrows its work to (Multi-Head
+ * Self-Attention section: softmax(Q K^T / sqrt(d_k)) for one head; Softmax
+ * section: the row softmax and its max-subtracted form, Eq. 1; fused-kernel
+ * section: Q and K are n x d_k, the output is the n x n matrix of attention
+ * weights).  Batch and head are independent repetitions of that problem.
+ *
+ * Conventions common to every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller; the library
+ *     never allocates, frees, copies to the host or synchronises.
+ *   - Arrays are dense row-major: Q, K are [B][H][N][d] (d fastest), P and S
+ *     are [B][H][N][N] (key index fastest) or [rows][cols] (cols fastest).
+ *   - `dtype` selects ONE element type for inputs and output: ATTNW_F32
+ *     (IEEE binary32) or ATTNW_BF16 (upper 16 bits of a binary32).  All
+ *     arithmetic between load and store is fp32 (bf16 inputs are multiplied on
+ *     the matrix cores with fp32 accumulation); bf16 results are rounded once,
+ *     to nearest even, at the store.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Work is enqueued on it and the call returns without waiting.
+ *   - Return value: ATTNW_OK (0) or a negative attnw_status.  Nothing throws or
+ *     aborts.  Arguments are validated before any HIP call, in this order:
+ *     null pointers, dtype, shape, supported sizes, 16-byte alignment of each
+ *     base pointer, overlap of output with inputs.  A dimension of 0 is an
+ *     empty problem: the call returns ATTNW_OK and launches nothing (pointers
+ *     are still checked for null only if the problem is non-empty).
+ *   - Inputs must be finite.  A NaN poisons its own row only.
+ *   - The library keeps no mutable global state; calls from several host
+ *     threads on different streams are safe.
+ */
+#ifndef ATTNW_H
+#define ATTNW_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ATTNW_F32 = 0,
+    ATTNW_BF16 = 1
+} attnw_dtype;
+
+typedef enum {
+    ATTNW_OK = 0,
+    ATTNW_ERR_NULL = -1,        /* a required pointer is NULL */
+    ATTNW_ERR_SHAPE = -2,       /* a negative dimension, or a product that overflows int64 */
+    ATTNW_ERR_DTYPE = -3,       /* dtype is neither ATTNW_F32 nor ATTNW_BF16 */
+    ATTNW_ERR_UNSUPPORTED = -4, /* d not a multiple of 16 or above 256; a dimension beyond the 32-bit grid limits */
+    ATTNW_ERR_ALIGN = -5,       /* a base pointer is not 16-byte aligned */
+    ATTNW_ERR_ALIAS = -6,       /* output overlaps an input */
+    ATTNW_ERR_LAUNCH = -7       /* the HIP runtime refused the launch */
+} attnw_status;
+
+/*
+ * Fused attention weights (matrix multiply + score scaling + row softmax in one
+ * kernel; only P is written to device memory -- the paper's fused kernel).
+ *
+ *   P[b][h][i][j] = exp(s_ij - m_i) / sum_k exp(s_ik - m_i),
+ *   s_ij = scale * sum_t Q[b][h][i][t] * K[b][h][j][t],   m_i = max_j s_ij.
+ *
+ * Q, K : [B][H][N][d], read only.         P : [B][H][N][N], written, never read.
+ * N >= 1 arbitrary; d a multiple of 16, 16 <= d <= 256; scale any finite float
+ * (0 gives the uniform 1/N, negative values are honoured).
+ * P must not overlap Q or K.
+ */
+int attnw_fused(const void *Q, const void *K, void *P,
+                int64_t B, int64_t H, int64_t N, int64_t d,
+                float scale, int dtype, void *stream);
+
+/*
+ * Dedicated row softmax over precomputed scores (the paper's Softmax kernel;
+ * Softmax section, Eq. 1):  P[r][j] = exp(S[r][j] - m_r) / sum_k exp(S[r][k] - m_r).
+ *
+ * S : [rows][cols], read only.            P : [rows][cols], written.
+ * rows, cols >= 1 arbitrary.  P == S exactly (in place) is allowed; any other
+ * overlap is ATTNW_ERR_ALIAS.
+ */
+int attnw_softmax(const void *S, void *P, int64_t rows, int64_t cols,
+                  int dtype, void *stream);
+
+/*
+ * First half of the unfused pair (matrix multiply + scaling as its own kernel,
+ * scores round-trip through device memory -- the pipeline the paper's fused
+ * kernel replaces):  S[b][h][i][j] = scale * sum_t Q[b][h][i][t] * K[b][h][j][t],
+ * rounded once to `dtype`.  attnw_softmax(S, P, B*H*N, N, ...) completes the pair.
+ * Same argument rules as attnw_fused.
+ */
+int attnw_gemm_scores(const void *Q, const void *K, void *S,
+                      int64_t B, int64_t H, int64_t N, int64_t d,
+                      float scale, int dtype, void *stream);
+
+/* Human-readable name of a status code; never NULL. */
+const char *attnw_status_string(int status);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int attnw_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ATTNW_H */

@@ -1,0 +1,175 @@
+/*
+ * attnw_oracle.c -- TEST INFRASTRUCTURE, not part of the product.
+ *
+ * Plain, slow, fp64 CPU statement of what the attention-weight path computes,
+ * written from the paper's definitions.  It shares no code, header, table or
+ * helper with the HIP library and must never be called from the product path:
+ * only the tests, the smoke check and the bench's cpu_baseline leg use it.
+ *
+ * What it follows:
+ *   - attention weights  P = softmax(Q K^T / sqrt(d_k))   (Multi-Head
+ *     Self-Attention section, definition of Attention(Q,K,V) without the V
+ *     product, and the fused-kernel section: Q and K are n x d_k, P is n x n);
+ *   - row softmax  sigma(Z)_ij = e^{Z_ij} / sum_k e^{Z_ik}   (Softmax section,
+ *     unnumbered definition; m x n input, one distribution per row);
+ *   - the max-subtracted form with m_i = max_j Z_ij   (Softmax section, Eq. 1),
+ *     which has the same value and keeps exp() away from overflow.
+ *
+ * Readings taken where the paper is silent (all listed in the design notes):
+ * the scale is the fp32 number the caller hands to the library, widened
+ * exactly; inputs (fp32 or bf16) are widened exactly to fp64, so the oracle is
+ * the true value of the function at the rounded inputs; dot products and row
+ * sums are accumulated left to right in fp64; exp is libm's.
+ *
+ * Parity pins (tests/test_oracle_pins.py): closed forms for N <= 4, row sums,
+ * uniform output for Q = 0, shift invariance (Eq. 1), key/query permutation,
+ * agreement of the plain definition with the max-subtracted form, and a
+ * cross-check against scipy/numpy on small cases.  Nothing here is unpinned.
+ *
+ * No blocking, fusion or reordering: every function is the definition, row by
+ * row.  OpenMP only splits independent rows across host threads.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_F64 = 2 };
+
+/* exact widening of one stored element to fp64 */
+static double load_elem(const void *base, int dtype, int64_t idx)
+{
+    switch (dtype) {
+    case ORACLE_F32:
+        return (double)((const float *)base)[idx];
+    case ORACLE_BF16: {
+        /* bf16 is the upper half of an fp32 */
+        uint32_t bits = (uint32_t)((const uint16_t *)base)[idx] << 16;
+        float f;
+        memcpy(&f, &bits, sizeof f);
+        return (double)f;
+    }
+    default:
+        return ((const double *)base)[idx];
+    }
+}
+
+static int g_threads_used = 1;
+
+/* number of host threads the last call actually ran on */
+int oracle_threads_used(void) { return g_threads_used; }
+
+static int pick_threads(int requested)
+{
+#ifdef _OPENMP
+    int t = requested > 0 ? requested : omp_get_max_threads();
+    return t < 1 ? 1 : t;
+#else
+    (void)requested;
+    return 1;
+#endif
+}
+
+/* Eq. 1 applied to one row of n scores, in place: z_j <- e^{z_j - m} / sum_k e^{z_k - m}. */
+static void softmax_row_inplace(double *z, int64_t n)
+{
+    double m = z[0];
+    for (int64_t j = 1; j < n; ++j)
+        if (z[j] > m) m = z[j];
+    double l = 0.0;
+    for (int64_t j = 0; j < n; ++j) {
+        z[j] = exp(z[j] - m);
+        l += z[j];
+    }
+    for (int64_t j = 0; j < n; ++j)
+        z[j] = z[j] / l;
+}
+
+/*
+ * Scaled attention scores of one head, rows [row_begin, row_end):
+ *   S_out[i - row_begin][j] = scale * sum_t Q[i][t] * K[j][t],  j = 0 .. N-1.
+ * Q, K: [N][d] row-major in `dtype`.  S_out: [(row_end-row_begin)][N] fp64.
+ */
+int oracle_scores(const void *Q, const void *K, int dtype, int64_t N, int64_t d, float scale,
+                  int64_t row_begin, int64_t row_end, double *S_out, int threads)
+{
+    if (!Q || !K || !S_out || N < 1 || d < 1 || row_begin < 0 || row_end > N || row_begin > row_end)
+        return -1;
+    const double c = (double)scale;
+    const int nt = pick_threads(threads);
+    g_threads_used = nt;
+#pragma omp parallel for schedule(static) num_threads(nt)
+    for (int64_t i = row_begin; i < row_end; ++i) {
+        double *out = S_out + (i - row_begin) * N;
+        for (int64_t j = 0; j < N; ++j) {
+            double acc = 0.0;
+            for (int64_t t = 0; t < d; ++t)
+                acc += load_elem(Q, dtype, i * d + t) * load_elem(K, dtype, j * d + t);
+            out[j] = c * acc;
+        }
+    }
+    return 0;
+}
+
+/*
+ * Attention weights of one head, rows [row_begin, row_end):
+ *   P_out[i - row_begin][:] = softmax_j( scale * sum_t Q[i][t] K[j][t] ).
+ */
+int oracle_attention_weights(const void *Q, const void *K, int dtype, int64_t N, int64_t d, float scale,
+                             int64_t row_begin, int64_t row_end, double *P_out, int threads)
+{
+    int rc = oracle_scores(Q, K, dtype, N, d, scale, row_begin, row_end, P_out, threads);
+    if (rc) return rc;
+    const int nt = pick_threads(threads);
+#pragma omp parallel for schedule(static) num_threads(nt)
+    for (int64_t r = 0; r < row_end - row_begin; ++r)
+        softmax_row_inplace(P_out + r * N, N);
+    return 0;
+}
+
+/*
+ * Row softmax of rows [row_begin, row_end) of a [rows][cols] matrix in `dtype`
+ * (Eq. 1).  P_out: [(row_end-row_begin)][cols] fp64.
+ */
+int oracle_softmax(const void *S, int dtype, int64_t rows, int64_t cols,
+                   int64_t row_begin, int64_t row_end, double *P_out, int threads)
+{
+    if (!S || !P_out || rows < 1 || cols < 1 || row_begin < 0 || row_end > rows || row_begin > row_end)
+        return -1;
+    const int nt = pick_threads(threads);
+    g_threads_used = nt;
+#pragma omp parallel for schedule(static) num_threads(nt)
+    for (int64_t i = row_begin; i < row_end; ++i) {
+        double *out = P_out + (i - row_begin) * cols;
+        for (int64_t j = 0; j < cols; ++j)
+            out[j] = load_elem(S, dtype, i * cols + j);
+        softmax_row_inplace(out, cols);
+    }
+    return 0;
+}
+
+/*
+ * The Softmax section's definition taken literally, with no max subtraction:
+ *   sigma(Z)_ij = e^{Z_ij} / sum_k e^{Z_ik}.
+ * Only safe for small-magnitude inputs; exists so that a test can pin Eq. 1
+ * (the two forms agree) against something other than the stable form itself.
+ */
+int oracle_softmax_plain(const void *S, int dtype, int64_t rows, int64_t cols, double *P_out)
+{
+    if (!S || !P_out || rows < 1 || cols < 1)
+        return -1;
+    for (int64_t i = 0; i < rows; ++i) {
+        double *out = P_out + i * cols;
+        double l = 0.0;
+        for (int64_t j = 0; j < cols; ++j) {
+            out[j] = exp(load_elem(S, dtype, i * cols + j));
+            l += out[j];
+        }
+        for (int64_t j = 0; j < cols; ++j)
+            out[j] = out[j] / l;
+    }
+    return 0;
+}
