@@ -23,10 +23,10 @@
  *     Work is enqueued on it and the call returns without waiting.
  *   - Return value: ATTNW_OK (0) or a negative attnw_status.  Nothing throws or
  *     aborts.  Arguments are validated before any HIP call, in this order:
- *     null pointers, dtype, shape, supported sizes, 16-byte alignment of each
- *     base pointer, overlap of output with inputs.  A dimension of 0 is an
- *     empty problem: the call returns ATTNW_OK and launches nothing (pointers
- *     are still checked for null only if the problem is non-empty).
+ *     dtype, negative dimensions, empty problem (a batch, head, row or column
+ *     count of 0: returns ATTNW_OK, launches nothing, pointers not looked at),
+ *     null pointers, size overflow, supported sizes, 16-byte alignment of each
+ *     base pointer, overlap of output with inputs.
  *   - Inputs must be finite.  A NaN poisons its own row only.
  *   - The library keeps no mutable global state; calls from several host
  *     threads on different streams are safe.

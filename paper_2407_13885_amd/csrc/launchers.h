@@ -1,0 +1,18 @@
+// Internal interface between the C-ABI layer and the kernel translation units.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace attnw {
+
+enum class DType : int { F32 = 0, BF16 = 1 };
+
+// Row softmax, arguments already validated.  Returns the launch status.
+hipError_t launch_softmax(DType dt, const void* S, void* P, int64_t rows, int64_t cols, hipStream_t stream);
+
+// Fused attention weights (scores_only = false) or scaled scores (scores_only = true).
+hipError_t launch_qk(DType dt, bool scores_only, const void* Q, const void* K, void* out,
+                     int64_t BH, int64_t N, int64_t d, float scale, hipStream_t stream);
+
+}  // namespace attnw

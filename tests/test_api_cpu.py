@@ -1,0 +1,123 @@
+"""Host-side checks that need no GPU: the C-ABI library loads, exports every
+symbol the header declares, and rejects bad arguments before any HIP call."""
+import ctypes
+import os
+import re
+import subprocess
+
+import pytest
+
+from paper_2407_13885_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "attnw.h")
+
+OK, E_NULL, E_SHAPE, E_DTYPE, E_UNSUP, E_ALIGN, E_ALIAS, E_LAUNCH = 0, -1, -2, -3, -4, -5, -6, -7
+F32, BF16 = 0, 1
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.library_path()):
+        binding.build()
+    return binding.load_library()
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(attnw_[a-z_]+)\s*\(", text)))
+
+
+def test_header_functions_are_exported(lib):
+    declared = _declared_functions()
+    assert set(declared) == set(binding.EXPORTS)
+    out = subprocess.run(["nm", "-D", "--defined-only", binding.library_path()], capture_output=True, text=True,
+                         check=True).stdout
+    exported = {line.split()[-1] for line in out.splitlines() if " T " in line}
+    for name in declared:
+        assert name in exported, name
+        assert getattr(lib, name) is not None
+
+
+def test_version_and_status_strings(lib):
+    assert binding.attnw_version() >= 100
+    seen = {binding.attnw_status_string(s) for s in range(0, -8, -1)}
+    assert len(seen) == 8 and "unknown status" not in seen
+    assert binding.attnw_status_string(-99) == "unknown status"
+
+
+# fake, suitably aligned, non-overlapping "device" addresses: validation never dereferences them
+QA, KA, PA = 0x10000000, 0x20000000, 0x40000000
+
+
+def test_fused_validation_order(lib):
+    f = lib.attnw_fused
+    assert f(QA, KA, PA, 1, 1, 128, 64, 0.125, 7, None) == E_DTYPE
+    assert f(None, None, None, 1, 1, 128, 64, 0.125, 7, None) == E_DTYPE          # dtype before null
+    assert f(QA, KA, PA, -1, 1, 128, 64, 0.125, BF16, None) == E_SHAPE
+    assert f(QA, KA, PA, 1, 1, -5, 64, 0.125, BF16, None) == E_SHAPE
+    assert f(None, KA, PA, 1, 1, 128, 64, 0.125, BF16, None) == E_NULL
+    assert f(QA, None, PA, 1, 1, 128, 64, 0.125, BF16, None) == E_NULL
+    assert f(QA, KA, None, 1, 1, 128, 64, 0.125, BF16, None) == E_NULL
+    assert f(QA, KA, PA, 1 << 40, 1 << 40, 128, 64, 0.125, BF16, None) == E_SHAPE  # B*H overflows
+    assert f(QA, KA, PA, 1 << 20, 1 << 20, 1 << 20, 64, 0.125, BF16, None) == E_SHAPE
+    for d in (0, 8, 24, 100, 272, 512):
+        assert f(QA, KA, PA, 1, 1, 128, d, 0.125, BF16, None) == E_UNSUP, d
+    assert f(QA, KA, PA, 1, 1, (1 << 30) + 1, 64, 0.125, BF16, None) == E_UNSUP
+    assert f(QA + 2, KA, PA, 1, 1, 128, 64, 0.125, BF16, None) == E_ALIGN
+    assert f(QA, KA + 8, PA, 1, 1, 128, 64, 0.125, BF16, None) == E_ALIGN
+    assert f(QA, KA, PA + 4, 1, 1, 128, 64, 0.125, F32, None) == E_ALIGN
+    # P overlapping Q / K: Q is 128*64*2 = 16384 bytes long
+    assert f(QA, KA, QA + 16384 - 16, 1, 1, 128, 64, 0.125, BF16, None) == E_ALIAS
+    assert f(QA, KA, KA, 1, 1, 128, 64, 0.125, BF16, None) == E_ALIAS
+    assert f(QA, PA + 128 * 128 * 2 - 16, PA, 1, 1, 128, 64, 0.125, BF16, None) == E_ALIAS
+
+
+def test_empty_problems_are_ok_and_touch_nothing(lib):
+    assert lib.attnw_fused(None, None, None, 0, 4, 128, 64, 0.125, BF16, None) == OK
+    assert lib.attnw_fused(None, None, None, 2, 0, 128, 64, 0.125, F32, None) == OK
+    assert lib.attnw_fused(None, None, None, 2, 2, 0, 64, 0.125, F32, None) == OK
+    assert lib.attnw_gemm_scores(None, None, None, 2, 2, 0, 64, 0.125, F32, None) == OK
+    assert lib.attnw_softmax(None, None, 0, 128, BF16, None) == OK
+    assert lib.attnw_softmax(None, None, 128, 0, F32, None) == OK
+
+
+def test_gemm_scores_shares_the_rules(lib):
+    g = lib.attnw_gemm_scores
+    assert g(QA, KA, PA, 1, 1, 128, 64, 0.125, 2, None) == E_DTYPE
+    assert g(QA, KA, None, 1, 1, 128, 64, 0.125, F32, None) == E_NULL
+    assert g(QA, KA, PA, 1, 1, 128, 20, 0.125, F32, None) == E_UNSUP
+    assert g(QA, KA, QA, 1, 1, 128, 64, 0.125, F32, None) == E_ALIAS
+
+
+def test_softmax_validation(lib):
+    s = lib.attnw_softmax
+    assert s(QA, PA, 4, 4, -1, None) == E_DTYPE
+    assert s(QA, PA, -4, 4, BF16, None) == E_SHAPE
+    assert s(QA, PA, 4, -4, BF16, None) == E_SHAPE
+    assert s(None, PA, 4, 4, BF16, None) == E_NULL
+    assert s(QA, None, 4, 4, BF16, None) == E_NULL
+    assert s(QA, PA, 1 << 40, 1 << 40, BF16, None) == E_SHAPE
+    assert s(QA, PA, (1 << 31), 8, BF16, None) == E_UNSUP
+    assert s(QA + 1, PA, 4, 4, BF16, None) == E_ALIGN
+    assert s(QA, PA + 8, 4, 4, F32, None) == E_ALIGN
+    assert s(QA, QA + 16, 4, 8, F32, None) == E_ALIAS          # partial overlap
+    # S == P exactly (in place) passes validation; it is exercised on the GPU
+
+
+def test_binding_raises_with_status(lib):
+    with pytest.raises(binding.AttnwError) as ei:
+        binding.attnw_softmax(QA + 1, PA, 4, 4, BF16)
+    assert ei.value.status == E_ALIGN and "aligned" in str(ei.value)
+
+
+def test_product_package_does_not_import_the_oracle():
+    """The oracle is test infrastructure: nothing under the product package may use it."""
+    pkg = os.path.join(ROOT, "paper_2407_13885_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for fn in files:
+            if fn.endswith((".py", ".hip", ".h", ".hpp", ".cpp", ".c")):
+                text = open(os.path.join(dirpath, fn)).read()
+                assert not re.search(r"^\s*(import|from)\s+oracle\b", text, flags=re.M), fn
+                assert "attnw_oracle" not in text, fn

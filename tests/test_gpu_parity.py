@@ -1,0 +1,169 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 CPU oracle on
+the same seeded inputs, element by element."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2407_13885_amd import workloads as wl
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _gpu():
+    gu.require_gpu()
+
+
+def _oracle_heads(x):
+    return oracle.attention_weights_bh(x.Q, x.K, x.dtype, x.scale)
+
+
+# ---- configuration 1: single head, fp32, N = 128, d = 64 ---------------------------------
+
+def test_c1_fused_fp32():
+    x = wl.c1()
+    P = gu.run_fused(x, guard=4096)
+    gu.check_weights(gu.to_f64(P), _oracle_heads(x), "f32", "c1 fused")
+
+
+def test_c1_softmax_fp32_on_oracle_scores():
+    """S = scale * Q K^T comes from the oracle, rounded once to fp32; the kernel's
+    output is held against the oracle softmax of that same S and against the
+    Q, K oracle itself."""
+    x = wl.c1()
+    s32 = oracle.scores(x.Q[0, 0], x.K[0, 0], "f32", x.scale).astype(np.float32)
+    P = gu.run_softmax(gu.to_dev(s32, "f32"), 128, 128, "f32", guard=4096)
+    got = gu.to_f64(P)
+    gu.check_weights(got, oracle.softmax(s32, "f32"), "f32", "c1 softmax vs oracle softmax")
+    gu.check_weights(got, _oracle_heads(x)[0, 0], "f32", "c1 softmax vs Q,K oracle")
+
+
+# ---- configuration 2 recipe, reduced rows: several blocks and a ragged last block --------
+
+def test_c2_recipe_small_bf16():
+    s = wl.c2(rows=1027)
+    P = gu.run_softmax(gu.to_dev(s.S, "bf16"), s.rows, s.cols, "bf16", guard=4096)
+    gu.check_weights(gu.to_f64(P), oracle.softmax(s.S, "bf16"), "bf16", "c2 recipe, 1027 rows")
+
+
+# ---- fused bf16, small shapes that span several tiles and ragged tails -------------------
+
+@pytest.mark.parametrize("B,H,N,d", [(1, 1, 256, 64), (2, 3, 320, 128), (1, 2, 1024, 64), (1, 1, 520, 32),
+                                     (1, 1, 200, 256), (1, 2, 136, 16), (1, 1, 72, 96)])
+def test_fused_bf16_small(B, H, N, d):
+    x = wl.fused_inputs("t", "bf16", B, H, N, d, seed=100 + N + d)
+    P = gu.run_fused(x, guard=8192)
+    gu.check_weights(gu.to_f64(P), _oracle_heads(x), "bf16", f"fused bf16 {B}x{H}x{N}x{d}")
+
+
+@pytest.mark.parametrize("N", [1, 2, 3, 4, 7, 17, 31, 33, 100, 129, 257])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_fused_ragged_n(N, dtype):
+    x = wl.fused_inputs("t", dtype, 1, 2, N, 64, seed=200 + N)
+    P = gu.run_fused(x, guard=4096)
+    gu.check_weights(gu.to_f64(P), _oracle_heads(x), dtype, f"fused {dtype} N={N}")
+
+
+@pytest.mark.parametrize("d", [16, 32, 48, 64, 80, 128, 192, 256])
+def test_fused_fp32_all_d(d):
+    x = wl.fused_inputs("t", "f32", 1, 1, 160, d, seed=300 + d)
+    P = gu.run_fused(x, guard=4096)
+    gu.check_weights(gu.to_f64(P), _oracle_heads(x), "f32", f"fused f32 d={d}")
+
+
+def test_fused_sharp_and_flat_rows_bf16():
+    """The long-row configuration's recipe (per-row factors in [0.5, 3]) at a size
+    the oracle covers in full: mixes near-uniform and sharply peaked rows."""
+    x = wl.fused_inputs("t", "bf16", 1, 2, 768, 64, seed=4, row_factor=(0.5, 3.0))
+    P = gu.run_fused(x, guard=4096)
+    gu.check_weights(gu.to_f64(P), _oracle_heads(x), "bf16", "sharp/flat rows")
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("scale", [0.0, -0.125, 0.5])
+def test_fused_scale_values(dtype, scale):
+    x = wl.fused_inputs("t", dtype, 1, 1, 192, 64, seed=17, scale=scale)
+    P = gu.run_fused(x, guard=4096)
+    ref = _oracle_heads(x)
+    # The 1e-6 bound belongs to scores of unit spread (scale = 1/sqrt(d)).  An fp32
+    # contraction of d terms leaves each scaled score with an error that grows like
+    # |scale| * sqrt(d), and p inherits it relatively: widen the bound by that factor.
+    abs_f32 = gu.ABS_F32 * max(1.0, abs(scale) * math.sqrt(64))
+    gu.check_weights(gu.to_f64(P), ref, dtype, f"scale {scale}", abs_f32=abs_f32)
+    if scale == 0.0:
+        assert np.allclose(gu.to_f64(P), 1.0 / 192, rtol=4e-3)
+
+
+def test_fused_zero_queries_uniform():
+    x = wl.fused_inputs("t", "bf16", 1, 1, 256, 64, seed=5)
+    x.Q[...] = 0
+    P = gu.to_f64(gu.run_fused(x))
+    assert np.array_equal(P, np.full_like(P, 1.0 / 256))      # 2^-8 is exact in bf16
+
+
+def test_fused_is_deterministic_and_heads_independent():
+    x = wl.fused_inputs("t", "bf16", 2, 2, 384, 64, seed=6)
+    a = gu.run_fused(x)
+    b = gu.run_fused(x)
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    y = wl.fused_inputs("t", "bf16", 2, 2, 384, 64, seed=6)
+    y.K[1, 0] = wl.fused_inputs("t", "bf16", 1, 1, 384, 64, seed=7).K[0, 0]
+    c = gu.run_fused(y)
+    same = [[torch.equal(a[i, j].view(torch.int16), c[i, j].view(torch.int16)) for j in range(2)] for i in range(2)]
+    assert same == [[True, True], [False, True]]
+
+
+# ---- dedicated softmax: every dispatch path, ragged and in place ----------------------------
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("cols", [1, 7, 8, 64, 520, 1000, 1024, 2049, 4096, 8192, 12288, 16384, 32768, 65536, 70000])
+def test_softmax_cols(dtype, cols):
+    rows = 9 if cols <= 16384 else 3
+    s = wl.softmax_inputs("t", dtype, rows, cols, seed=400 + cols, sigma=2.0, peak_fraction=0.01)
+    P = gu.run_softmax(gu.to_dev(s.S, dtype), rows, cols, dtype, guard=4096)
+    gu.check_weights(gu.to_f64(P), oracle.softmax(s.S, dtype), dtype, f"softmax {dtype} cols={cols}")
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("cols", [2048, 1001])
+def test_softmax_in_place(dtype, cols):
+    s = wl.softmax_inputs("t", dtype, 21, cols, seed=500 + cols, sigma=2.0, peak_fraction=0.01)
+    S = gu.to_dev(s.S, dtype)
+    P = gu.run_softmax(S, 21, cols, dtype, inplace=True)
+    assert P.data_ptr() == S.data_ptr()
+    gu.check_weights(gu.to_f64(P), oracle.softmax(s.S, dtype), dtype, f"in-place {dtype} cols={cols}")
+
+
+def test_softmax_large_offsets_fp32():
+    """Eq. 1: a large common offset per row must cancel (fp32 keeps the 1e-6 bound)."""
+    s = wl.softmax_inputs("t", "f32", 16, 512, seed=9, sigma=1.5)
+    shifted = (s.S.astype(np.float64) + 1000.0 * (1 + np.arange(16)).reshape(16, 1)).astype(np.float32)
+    P = gu.run_softmax(gu.to_dev(shifted, "f32"), 16, 512, "f32")
+    gu.check_weights(gu.to_f64(P), oracle.softmax(shifted, "f32"), "f32", "shifted rows")
+
+
+# ---- unfused pair: stage-wise parity --------------------------------------------------------
+
+@pytest.mark.parametrize("dtype,N,d", [("bf16", 320, 64), ("bf16", 129, 128), ("f32", 200, 64), ("f32", 128, 256)])
+def test_gemm_scores_and_unfused_pair(dtype, N, d):
+    x = wl.fused_inputs("t", dtype, 1, 2, N, d, seed=600 + N)
+    S = gu.run_scores(x, guard=4096)
+    got = gu.to_f64(S)
+    Qa, Ka = np.abs(wl.widen(x.Q, dtype)), np.abs(wl.widen(x.K, dtype))
+    for h in range(2):
+        ref = oracle.scores(x.Q[0, h], x.K[0, h], dtype, x.scale)
+        # fp32 accumulation of d products: |err| <= d * 2^-24 * scale * sum|q||k| (first order),
+        # then one rounding to the storage type
+        acc_bound = d * 2.0 ** -24 * float(x.scale) * (Qa[0, h] @ Ka[0, h].T)
+        store = (2.0 ** -8 if dtype == "bf16" else 2.0 ** -24) * np.abs(ref)
+        assert (np.abs(got[0, h] - ref) <= acc_bound + store + 1e-30).all(), f"scores {dtype} head {h}"
+    # second stage on the S actually produced
+    P = gu.run_softmax(S.view(2 * N, N), 2 * N, N, dtype)
+    s_host = S.view(2 * N, N).cpu()
+    s_np = s_host.numpy() if dtype == "f32" else s_host.view(torch.int16).numpy().view(np.uint16)
+    gu.check_weights(gu.to_f64(P), oracle.softmax(s_np, dtype), dtype, f"unfused softmax {dtype}")
