@@ -1,0 +1,271 @@
+#!/usr/bin/env python3
+"""Benchmark of the attention-weight path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4]
+
+One "step" is one call of the library on one batch of seeded synthetic input
+already resident in HBM.  The headline workload (top-level ``value``) is the
+fused kernel on configuration c4 (B=1 H=16 N=4096 d=128 bf16, the paper's d_k
+and its largest fused n); the same JSON line carries, under ``workloads``, the
+dedicated softmax on c2, the fused kernel on c3 and c5, and the unfused pair
+(score GEMM, then softmax) on c3..c5 for the fused-vs-unfused ratio.
+
+Timing: W untimed calls, then exactly K calls bracketed by a device
+synchronisation on both sides (wall clock -> ``ms_per_step`` and ``value``) and
+by HIP events recorded on the stream the kernels are launched on (-> the
+average launch duration used for the roofline).  Working sets smaller than the
+256 MB last-level cache are rotated through distinct buffers (> 1 GiB in total)
+so that no call finds its data on chip.
+
+The CPU oracle is timed in the same run on the host cores (``cpu_baseline``):
+a reported baseline, not the target.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "attention-weight elements/s and achieved HBM GB/s (% of peak), fused vs unfused"
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+ROTATE_BYTES = 1.25 * 2 ** 30  # rotate small working sets through at least this much memory
+CACHE_BYTES = 256e6
+
+
+def _dev(a, dtype):
+    import numpy as np
+    import torch
+    if dtype == "f32":
+        return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def _time_calls(call, n_sets, steps, warmup):
+    """call(i) launches one step on buffer set i % n_sets.  Returns (wall ms/step, event ms/step)."""
+    import torch
+    stream = torch.cuda.current_stream()
+    for i in range(warmup):
+        call(i % n_sets)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for i in range(steps):
+        call((warmup + i) % n_sets)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
+
+
+def _n_sets(set_bytes):
+    if set_bytes >= 2 * CACHE_BYTES:
+        return 2
+    return int(math.ceil(ROTATE_BYTES / set_bytes))
+
+
+def _record(name, what, elements, alg_bytes, wall_ms, ev_ms, n_sets):
+    gbs = alg_bytes / (ev_ms * 1e-3) * 1e-9
+    return {
+        "workload": name, "call": what, "elements": elements, "algorithmic_bytes": alg_bytes,
+        "ms_per_step": round(wall_ms, 5), "kernel_ms": round(ev_ms, 5),
+        "elements_per_s": elements / (wall_ms * 1e-3),
+        "hbm_GBps": round(gbs, 1), "hbm_frac_of_peak": round(gbs / HBM_PEAK_GBS, 4), "buffer_sets": n_sets,
+    }
+
+
+def bench_softmax(cfg, steps, warmup):
+    import torch
+    import paper_2407_13885_amd as attnw
+    x = cfg()
+    dt = attnw.ATTNW_BF16 if x.dtype == "bf16" else attnw.ATTNW_F32
+    n_sets = _n_sets(x.algorithmic_bytes)
+    S0 = _dev(x.S, x.dtype)
+    S = [S0] + [S0.clone() for _ in range(n_sets - 1)]
+    P = [torch.empty_like(S0) for _ in range(n_sets)]
+    stream = torch.cuda.current_stream()
+
+    def call(i):
+        attnw.attnw_softmax(S[i], P[i], x.rows, x.cols, dt, stream)
+
+    wall, ev = _time_calls(call, n_sets, steps, warmup)
+    rs = float((P[0].float().sum(-1) - 1.0).abs().max().item())
+    rec = _record(x.name, "attnw_softmax", x.elements, x.algorithmic_bytes, wall, ev, n_sets)
+    rec["max_row_sum_error"] = rs
+    rec["shape"] = {"rows": x.rows, "cols": x.cols, "dtype": x.dtype}
+    return rec, x
+
+
+def bench_fused(cfg, steps, warmup, with_unfused=True):
+    import torch
+    import paper_2407_13885_amd as attnw
+    x = cfg()
+    dt = attnw.ATTNW_BF16 if x.dtype == "bf16" else attnw.ATTNW_F32
+    tdt = torch.bfloat16 if x.dtype == "bf16" else torch.float32
+    Q, K = _dev(x.Q, x.dtype), _dev(x.K, x.dtype)
+    out_bytes = x.elements * x.itemsize
+    n_sets = _n_sets(out_bytes)
+    shape = (x.B, x.H, x.N, x.N)
+    P = [torch.empty(shape, dtype=tdt, device="cuda") for _ in range(n_sets)]
+    stream = torch.cuda.current_stream()
+    scale = float(x.scale)
+
+    def call(i):
+        attnw.attnw_fused(Q, K, P[i], x.B, x.H, x.N, x.d, scale, dt, stream)
+
+    wall, ev = _time_calls(call, n_sets, steps, warmup)
+    rec = _record(x.name, "attnw_fused", x.elements, x.algorithmic_bytes, wall, ev, n_sets)
+    rec["shape"] = {"B": x.B, "H": x.H, "N": x.N, "d": x.d, "dtype": x.dtype}
+    rec["mfma_TFLOPs_two_pass"] = round(2 * 2.0 * x.elements * x.d / (ev * 1e-3) * 1e-12, 1)
+    # row sums of every row (a property that needs no oracle)
+    worst = 0.0
+    for b in range(x.B):
+        for h in range(x.H):
+            worst = max(worst, float((P[0][b, h].float().sum(-1) - 1.0).abs().max().item()))
+    rec["max_row_sum_error"] = worst
+
+    if with_unfused:
+        # unfused pair: scores round-trip through HBM in the storage dtype
+        S = [torch.empty(shape, dtype=tdt, device="cuda") for _ in range(n_sets)]
+        rows = x.B * x.H * x.N
+
+        def call_gemm(i):
+            attnw.attnw_gemm_scores(Q, K, S[i], x.B, x.H, x.N, x.d, scale, dt, stream)
+
+        def call_sm(i):
+            attnw.attnw_softmax(S[i], P[i], rows, x.N, dt, stream)
+
+        def call_pair(i):
+            call_gemm(i)
+            call_sm(i)
+
+        wall_p, ev_p = _time_calls(call_pair, n_sets, steps, warmup)
+        _, ev_g = _time_calls(call_gemm, n_sets, steps, warmup)
+        _, ev_s = _time_calls(call_sm, n_sets, steps, warmup)
+        unf_bytes = x.algorithmic_bytes + 2 * out_bytes      # + write S, read S
+        rec["unfused"] = {
+            "ms_per_step": round(wall_p, 5), "kernel_ms": round(ev_p, 5),
+            "gemm_scores_ms": round(ev_g, 5), "softmax_ms": round(ev_s, 5),
+            "elements_per_s": x.elements / (wall_p * 1e-3),
+            "algorithmic_bytes": unf_bytes, "hbm_GBps": round(unf_bytes / (ev_p * 1e-3) * 1e-9, 1),
+        }
+        rec["fused_vs_unfused_speedup"] = round(ev_p / ev, 3)
+        del S
+    del P
+    torch.cuda.empty_cache()
+    return rec, x
+
+
+def cpu_baseline_fused(x, rows_per_head=1024):
+    """The oracle as it stands, on the host cores, on a bounded sample of the workload."""
+    import oracle
+    rows_per_head = min(rows_per_head, x.N)
+    # touch the library once so that its build/load is not timed
+    oracle.attention_weights(x.Q[0, 0], x.K[0, 0], x.dtype, x.scale, rows=(0, 1))
+    t0 = time.perf_counter()
+    done = 0
+    for b in range(x.B):
+        for h in range(x.H):
+            oracle.attention_weights(x.Q[b, h], x.K[b, h], x.dtype, x.scale, rows=(0, rows_per_head))
+            done += rows_per_head
+    dt = time.perf_counter() - t0
+    return {
+        "value": done * x.N / dt, "unit": "elements/s", "cores": oracle.threads_used(), "kind": "oracle",
+        "sample": f"first {rows_per_head} query rows of each of the {x.B * x.H} heads of {x.name} "
+                  f"({done} of {x.B * x.H * x.N} rows, {dt:.2f} s wall), fp64, all keys",
+        "seconds": round(dt, 3),
+    }
+
+
+def cpu_baseline_softmax(x, rows=8192):
+    import oracle
+    rows = min(rows, x.rows)
+    oracle.softmax(x.S, x.dtype, rows=(0, 1))
+    t0 = time.perf_counter()
+    oracle.softmax(x.S, x.dtype, rows=(0, rows))
+    dt = time.perf_counter() - t0
+    return {
+        "value": rows * x.cols / dt, "unit": "elements/s", "cores": oracle.threads_used(), "kind": "oracle",
+        "sample": f"first {rows} of {x.rows} rows of {x.name} ({dt:.2f} s wall), fp64",
+        "seconds": round(dt, 3),
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c4", choices=["c2", "c3", "c4", "c5"],
+                    help="configuration reported at the top level of the JSON line")
+    ap.add_argument("--only", action="store_true", help="measure the headline workload only")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (heads and query rows shard with no exchange; "
+              "see DESIGN.md); run it with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2407_13885_amd as attnw
+    from paper_2407_13885_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    attnw.load_library()   # raises if libattnw.so is missing: there is no fallback
+    torch.cuda.set_device(0)
+
+    order = ["c2", "c3", "c4", "c5"]
+    todo = [args.workload] if args.only else order
+    results, inputs = {}, {}
+    for name in todo:
+        print(f"[bench] {name} ...", file=sys.stderr, flush=True)
+        if name == "c2":
+            results[name], inputs[name] = bench_softmax(wl.c2, args.steps, args.warmup)
+        else:
+            results[name], inputs[name] = bench_fused(wl.CONFIGS[name], args.steps, args.warmup)
+        if name != args.workload:
+            inputs.pop(name)
+
+    head = results[args.workload]
+    x = inputs[args.workload]
+    cpu = None
+    if not args.no_cpu_baseline:
+        print("[bench] cpu_baseline (oracle on host cores) ...", file=sys.stderr, flush=True)
+        cpu = cpu_baseline_softmax(x) if args.workload == "c2" else cpu_baseline_fused(x)
+
+    dominant = "softmax_rows_kernel" if args.workload == "c2" else "qk_kernel"
+    line = {
+        "metric": METRIC,
+        "value": head["elements_per_s"],
+        "unit": "elements/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",     # arithmetic type between load and store (bf16 operands on the matrix cores, fp32 accumulate)
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {head['call']} {json.dumps(head['shape'])}",
+                   "generator": wl.GENERATOR_ID, "buffer_sets": head["buffer_sets"]},
+        "roofline": {"bound": "hbm", "kernel": dominant, "achieved": head["hbm_GBps"], "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": head["hbm_frac_of_peak"], "traffic": None},
+        "cpu_baseline": cpu,
+        "fused_vs_unfused_speedup": {k: v.get("fused_vs_unfused_speedup") for k, v in results.items()
+                                     if "fused_vs_unfused_speedup" in v},
+        "workloads": results,
+    }
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -43,8 +43,8 @@ int run_qk(bool scores_only, const void* Q, const void* K, void* out, int64_t B,
     if (mul_overflows(in_elems, es, &in_bytes) || mul_overflows(out_elems, es, &out_bytes)) return ATTNW_ERR_SHAPE;
     if (d < 16 || d > 256 || (d % 16) != 0) return ATTNW_ERR_UNSUPPORTED;
     if (N > (int64_t)1 << 30) return ATTNW_ERR_UNSUPPORTED;
-    // one workgroup per (head, 128-query strip), grid padded to a multiple of 8
-    const int64_t strips = (N + 127) / 128;
+    // one workgroup per (head, strip of at least 64 queries), grid padded to a multiple of 8
+    const int64_t strips = (N + 63) / 64;
     int64_t tiles;
     if (mul_overflows(BH, strips, &tiles) || tiles > (int64_t)std::numeric_limits<int32_t>::max() - 8)
         return ATTNW_ERR_UNSUPPORTED;

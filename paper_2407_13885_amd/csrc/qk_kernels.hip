@@ -13,15 +13,24 @@
 // weights with one fused multiply-add and one 2^x per element, rounds once and
 // streams them to HBM.  Scores never leave the registers.
 //
+// Work split inside a workgroup of WQ x WK waves: wave (wq, wk) owns QW = 32*QB
+// queries (strip rows wq*QW ...) and, of every K tile of BN = 32*SUBS*WK keys,
+// the SUBS 32-key sub-tiles wk*SUBS ...; partial row maxima / sums of the WK
+// waves that share a query meet once, in LDS, between the passes -- the same
+// local-then-global reduction the paper runs across a row of cores.
+//
 // Orientation: the MFMA computes the TRANSPOSED tile  (K tile) * (Q strip)^T, so
 // that a lane's 16 accumulators are 16 keys of ONE query: row reductions stay
-// inside the lane (plus one exchange between lanes l and l+32 at the end of pass
-// one) and every lane owns runs of 4 consecutive keys for the store.
+// inside the lane (plus one exchange between lanes l and l+32) and every lane
+// owns runs of 4 consecutive keys for the store.
 #include "device_utils.h"
 #include "launchers.h"
 
 namespace attnw {
 namespace {
+
+typedef const void __attribute__((address_space(1)))* global_cptr;
+typedef void __attribute__((address_space(3)))* lds_ptr;
 
 template <typename T> struct Mma;
 
@@ -49,34 +58,70 @@ template <> struct Mma<float> {
     static constexpr uint32_t kSignMask = 0x80000000u;
 };
 
+// vmcnt(0) with the other counters left alone (gfx9 encoding of s_waitcnt)
+__device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
+// 16 bytes per lane from global memory straight into LDS (lane i lands at dst + 16*i;
+// dst is wave-uniform).  The __restrict__ parameters give the transfer an alias scope of
+// its own once inlined, which is what lets the compiler see that LDS reads from the
+// OTHER tile buffer need not wait for it.
+__device__ __forceinline__ void dma16(const char* __restrict__ src, char* __restrict__ dst)
+{
+    __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)dst, 16, 0, 0);
+}
+
+template <int I> struct IC { static constexpr int value = I; };
+
+// Calls body(tile, IC<buffer>) for tile = 0 .. n-1 with the LDS buffer alternating from
+// `first`; the buffer is a compile-time constant inside body.
+template <typename Body>
+__device__ __forceinline__ void for_tiles(int first, int n, Body&& body)
+{
+    int t = 0;
+    if (first == 1 && n > 0) { body(t, IC<1>{}); ++t; }
+    for (; t + 1 < n; t += 2) {
+        body(t, IC<0>{});
+        body(t + 1, IC<1>{});
+    }
+    if (t < n) body(t, IC<0>{});
+}
+
 // T      element type (uint16_t = bf16 bits, float)
 // DB     padded bytes of one Q/K row held on chip (power of two, >= d * sizeof(T))
-// BN     keys per LDS tile
-// QB     32-query blocks per wave (a workgroup of 4 waves owns BM = 128 * QB queries)
+// QB     32-query blocks per wave
+// WQ,WK  waves along queries / along the keys of a tile
+// SUBS   32-key sub-tiles per wave per K tile
 // SCORES true: write scale * Q K^T (one pass); false: write the attention weights
-template <typename T, int DB, int BN, int QB, bool SCORES>
-__global__ __launch_bounds__(256, 2)
+// FAST   true: N is a multiple of the strip and of the K tile and rows are exactly
+//        DB bytes, so no masking, clamping or store predicate is compiled in
+template <typename T, int DB, int QB, int WQ, int WK, int SUBS, bool SCORES, bool FAST>
+__global__ __launch_bounds__(64 * WQ * WK)
 void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__ out,
                int N, int d, float c, uint32_t sign_flip, uint32_t strips, uint32_t total_tiles)
 {
     constexpr int ES = sizeof(T);
     constexpr int EPC = 16 / ES;              // elements per 16-byte chunk
+    constexpr int NW = WQ * WK;               // waves per workgroup
     constexpr int QW = 32 * QB;               // queries per wave
-    constexpr int BM = 4 * QW;                // queries per workgroup
+    constexpr int BM = QW * WQ;               // queries per workgroup
+    constexpr int BN = 32 * SUBS * WK;        // keys per LDS tile
     constexpr int G = DB / 32;                // 32-byte contraction groups per row
     constexpr int CPR = DB / 16;              // chunks per K row in LDS
-    constexpr int KT = BN / 32;               // 32-key sub-tiles per K tile
     constexpr int K_TILE_BYTES = BN * DB;
-    constexpr int LPT = BN * CPR / 256;       // K chunks each thread stages per tile
-    constexpr int ST_PITCH = BN * ES + 16;    // staging row pitch (padded against bank conflicts)
+    constexpr int LOADS = BN * CPR / 64 / NW; // 1-KiB wave loads each wave issues per tile
+    constexpr int SEG = 32 * SUBS * ES;       // bytes of one staged row: the wave's keys of one tile
+    constexpr int ST_PITCH = SEG + 16;        // padded against bank conflicts
     constexpr int ST_BYTES = QW * ST_PITCH;
-    constexpr int CPS = BN * ES / 16;         // chunks per staging row
-    constexpr int RPI = 64 / CPS;             // staging rows one store instruction covers
+    constexpr int CPS = SEG / 16;             // chunks per staged row
+    constexpr int RPI = 64 / CPS;             // staged rows one store instruction covers
     constexpr int RPL = CPR >= 16 ? 1 : 16 / CPR;           // K rows per 256-byte LDS line
     constexpr int SWZ_MASK = (CPR >= 16 ? 16 : CPR) - 1;
-    static_assert(BN % 32 == 0 && (BN * CPR) % 256 == 0 && CPS <= 64 && QW % RPI == 0, "tile shape");
+    static_assert((BN * CPR) % (64 * NW) == 0 && CPS <= 64 && QW % RPI == 0, "tile shape");
 
-    __shared__ __align__(16) char smem[2 * K_TILE_BYTES + 4 * ST_BYTES];
+    __shared__ __align__(16) char k_lds0[K_TILE_BYTES];   // the two K tile buffers are separate
+    __shared__ __align__(16) char k_lds1[K_TILE_BYTES];   // objects: see dma16
+    __shared__ __align__(16) char st_lds[NW * ST_BYTES];
+    __shared__ float stat_lds[SCORES ? 2 : NW * QW * 2];
 
     const uint32_t logical = xcd_contiguous_block_id(blockIdx.x, gridDim.x);
     if (logical >= total_tiles) return;
@@ -85,18 +130,18 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6;
+    const int wq = wave / WK, wk = wave % WK;
     const int lane = tid & 63;
     const int l32 = lane & 31;
     const int half = lane >> 5;
 
-    const int cpr_act = d * ES / 16;          // chunks of real data per row
-    const int64_t row_bytes = (int64_t)d * ES;
+    const int cpr_act = FAST ? CPR : d * ES / 16;   // chunks of real data per row
+    const int row_bytes = FAST ? DB : d * ES;
     const char* Qh = reinterpret_cast<const char*>(Q) + (int64_t)bh * N * row_bytes;
     const char* Kh = reinterpret_cast<const char*>(K) + (int64_t)bh * N * row_bytes;
     T* out_h = out + (int64_t)bh * N * N;
-    const int qw0 = strip * BM + wave * QW;   // first query of this wave
-
-    char* const stage = smem + 2 * K_TILE_BYTES + wave * ST_BYTES;
+    const int qw0 = strip * BM + wq * QW;     // first query of this wave
+    char* const stage = st_lds + wave * ST_BYTES;
 
     // ---- Q fragments: registers for the whole kernel --------------------------------
     u32x4 qf[QB][G];
@@ -107,43 +152,53 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
         for (int g = 0; g < G; ++g) {
             const int cq = 2 * g + half;
             u32x4 v = {0u, 0u, 0u, 0u};
-            if (q < N && cq < cpr_act) v = *reinterpret_cast<const u32x4*>(Qh + (int64_t)q * row_bytes + cq * 16);
+            if (FAST || (q < N && cq < cpr_act))
+                v = *reinterpret_cast<const u32x4*>(Qh + (int64_t)q * row_bytes + cq * 16);
             qf[qb][g] = v ^ sign_flip;        // negative scale: softmax(-|c| s) = softmax(|c| (-Q) K^T)
         }
     }
 
-    // ---- K tile staging ----------------------------------------------------------------
+    // ---- K tiles: global memory -> LDS directly, 16 bytes per lane ------------------------
+    // A wave-wide load fills 1 KiB of consecutive LDS; LDS slot s holds chunk
+    // (key, ch) with s = key * CPR + (ch ^ swizzle(key)), so the swizzle that keeps
+    // the MFMA operand reads conflict-free is applied to the global address.
+    int key_of[LOADS], goff[LOADS];
+#pragma unroll
+    for (int j = 0; j < LOADS; ++j) {
+        const int s = (wave + NW * j) * 64 + lane;
+        const int key = s / CPR;
+        int ch = (s % CPR) ^ ((key / RPL) & SWZ_MASK);
+        ch = ch < cpr_act ? ch : 0;           // padding columns are never read: any valid address
+        key_of[j] = key;
+        goff[j] = key * row_bytes + ch * 16;
+    }
     const int n_tiles = (N + BN - 1) / BN;
-    u32x4 kreg[LPT];
-    auto k_fetch = [&](int tile) {
+    // Every workgroup starts its sweep over the keys at a different tile and wraps
+    // around.  With all workgroups marching in step, the rows they write at one moment
+    // sit a whole row pitch apart and land on the same few memory channels; the
+    // stagger spreads the store stream over all of them.
+    const int rot = (int)((logical * 7u) % (uint32_t)n_tiles);
+    auto tile_at = [&](int j) { const int t = j + rot; return t >= n_tiles ? t - n_tiles : t; };
+    auto k_issue = [&](int tile, auto bufc) {
+        char* const k_buf = decltype(bufc)::value == 0 ? k_lds0 : k_lds1;
         const int k0 = tile * BN;
+        const char* tile_base = Kh + (int64_t)k0 * row_bytes;
 #pragma unroll
-        for (int j = 0; j < LPT; ++j) {
-            const int ci = tid + 256 * j;
-            const int key = ci / CPR, ch = ci % CPR;
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (k0 + key < N && ch < cpr_act)
-                v = *reinterpret_cast<const u32x4*>(Kh + (int64_t)(k0 + key) * row_bytes + ch * 16);
-            kreg[j] = v;
-        }
-    };
-    auto k_commit = [&](int buf) {
-        char* base = smem + buf * K_TILE_BYTES;
-#pragma unroll
-        for (int j = 0; j < LPT; ++j) {
-            const int ci = tid + 256 * j;
-            const int key = ci / CPR, ch = ci % CPR;
-            const int sw = ch ^ ((key / RPL) & SWZ_MASK);
-            *reinterpret_cast<u32x4*>(base + key * DB + sw * 16) = kreg[j];
+        for (int j = 0; j < LOADS; ++j) {
+            const char* src = tile_base + goff[j];
+            if (!FAST && k0 + BN > N) {       // last tile: keys past the end re-read key N-1 (masked later)
+                const int kk = min(k0 + key_of[j], N - 1);
+                src = Kh + (int64_t)kk * row_bytes + (goff[j] - key_of[j] * row_bytes);
+            }
+            dma16(src, k_buf + (wave + NW * j) * 1024);
         }
     };
 
-    // scores of sub-tile kt of the tile in `buf`: acc[qb][r] = q . k for key
-    // kt*32 + 8*(r/4) + 4*half + r%4 and query qb*32 + l32
-    auto mma_subtile = [&](int buf, int kt, f32x16 (&acc)[QB]) {
-        const char* base = smem + buf * K_TILE_BYTES;
-        const int key = kt * 32 + l32;
-        const char* rowp = base + key * DB;
+    // scores of 32-key sub-tile `sub` of the tile in `buf`: acc[qb][r] = q . k for key
+    // sub*32 + 8*(r/4) + 4*half + r%4 and query qb*32 + l32
+    auto mma_subtile = [&](auto bufc, int sub, f32x16 (&acc)[QB]) {
+        const int key = sub * 32 + l32;
+        const char* rowp = (decltype(bufc)::value == 0 ? k_lds0 : k_lds1) + key * DB;
         const int swz = (key / RPL) & SWZ_MASK;
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb)
@@ -151,7 +206,7 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
             for (int r = 0; r < 16; ++r) acc[qb][r] = 0.0f;
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            if (2 * g < cpr_act) {            // wave-uniform: skip the zero padding of short rows
+            if (FAST || 2 * g < cpr_act) {    // wave-uniform: skip the padding of short rows
                 const u32x4 a = *reinterpret_cast<const u32x4*>(rowp + (((2 * g + half) ^ swz) * 16));
 #pragma unroll
                 for (int qb = 0; qb < QB; ++qb) Mma<T>::run(acc[qb], a, qf[qb][g]);
@@ -159,36 +214,35 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
         }
     };
 
-    // move the wave's staged QW x BN block to global memory, 16 bytes per lane
-    const bool vec_ok = (N % EPC) == 0;
-    auto flush_stage = [&](int k0) {
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    // move the wave's staged QW x (32*SUBS) block to global memory, 16 bytes per lane
+    const bool vec_ok = FAST || (N % EPC) == 0;
+    T* const out_lane = out_h + (int64_t)(qw0 + lane / CPS) * N + (lane % CPS) * EPC;
+    auto flush_stage = [&](int kseg0) {
 #pragma unroll
         for (int it = 0; it < QW / RPI; ++it) {
             const int row = it * RPI + lane / CPS;
-            const int ch = lane % CPS;
-            const int q = qw0 + row;
-            const int key0 = k0 + ch * EPC;
-            const u32x4 v = *reinterpret_cast<const u32x4*>(stage + row * ST_PITCH + ch * 16);
-            if (q < N && key0 < N) {
-                T* dst = out_h + (int64_t)q * N + key0;
-                if (vec_ok) {
-                    __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(dst));
-                } else {
-                    const T* e = reinterpret_cast<const T*>(&v);
+            const u32x4 v = *reinterpret_cast<const u32x4*>(stage + row * ST_PITCH + (lane % CPS) * 16);
+            T* dst = out_lane + (int64_t)(it * RPI) * N + kseg0;
+            if constexpr (FAST) {
+                *reinterpret_cast<u32x4*>(dst) = v;
+            } else {
+                const int q = qw0 + row;
+                const int key0 = kseg0 + (lane % CPS) * EPC;
+                if (q < N && key0 < N) {
+                    if (vec_ok) {
+                        *reinterpret_cast<u32x4*>(dst) = v;
+                    } else {
+                        const T* e = reinterpret_cast<const T*>(&v);
 #pragma unroll
-                    for (int i = 0; i < EPC; ++i)
-                        if (key0 + i < N) dst[i] = e[i];
+                        for (int i = 0; i < EPC; ++i)
+                            if (key0 + i < N) dst[i] = e[i];
+                    }
                 }
             }
         }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
     };
-    auto stage_put4 = [&](int qb, int kt, int r4, float v0, float v1, float v2, float v3) {
-        char* p = stage + (qb * 32 + l32) * ST_PITCH + (kt * 32 + 8 * r4 + 4 * half) * ES;
+    auto stage_put4 = [&](int qb, int u, int r4, float v0, float v1, float v2, float v3) {
+        char* p = stage + (qb * 32 + l32) * ST_PITCH + (u * 32 + 8 * r4 + 4 * half) * ES;
         if constexpr (ES == 2) {
             u32x2 w = {pack_bf16x2(v0, v1), pack_bf16x2(v2, v3)};
             *reinterpret_cast<u32x2*>(p) = w;
@@ -198,40 +252,28 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
         }
     };
 
-    // ---- software pipeline over K tiles: fetch t+1 while computing t -------------------
-    const int passes = SCORES ? 1 : 2;
-    const int steps = passes * n_tiles;
     float m_run[QB], l_run[QB], bias[QB];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) { m_run[qb] = kNegBig; l_run[qb] = 0.0f; bias[qb] = 0.0f; }
 
-    k_fetch(0);
-    k_commit(0);
+    k_issue(tile_at(0), IC<0>{});
+    wait_vmem();
     __syncthreads();
 
-    for (int s = 0; s < steps; ++s) {
-        const int tile = (s >= n_tiles) ? s - n_tiles : s;
-        const bool second = s >= n_tiles;
-        const int buf = s & 1;
-        const int k0 = tile * BN;
-        const bool tail = k0 + BN > N;
-        if (s + 1 < steps) k_fetch((s + 1 >= n_tiles) ? s + 1 - n_tiles : s + 1);
-
+    if constexpr (!SCORES) {
+        // ================= pass one: running row maximum and sum of exponentials (Eq. 1) =========
+        for_tiles(0, n_tiles, [&](int j, auto buf) {
+            const int tile = tile_at(j);
+            const int k0 = tile * BN;
+            const bool tail = !FAST && k0 + BN > N;
+            k_issue(tile_at(j + 1 < n_tiles ? j + 1 : 0), IC<1 - decltype(buf)::value>{});   // pass two starts over
 #pragma unroll
-        for (int kt = 0; kt < KT; ++kt) {
-            if (k0 + kt * 32 >= N) break;     // uniform: nothing but padding left in this tile
-            f32x16 acc[QB];
-            mma_subtile(buf, kt, acc);
-            const int kbase = k0 + kt * 32 + 4 * half;
-            if constexpr (SCORES) {
-#pragma unroll
-                for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-                    for (int r4 = 0; r4 < 4; ++r4)
-                        stage_put4(qb, kt, r4, acc[qb][4 * r4] * c, acc[qb][4 * r4 + 1] * c,
-                                   acc[qb][4 * r4 + 2] * c, acc[qb][4 * r4 + 3] * c);
-            } else if (!second) {
-                // pass one: running maximum and sum of exponentials (Eq. 1), per lane
+            for (int u = 0; u < SUBS; ++u) {
+                const int sub = wk * SUBS + u;
+                if (!FAST && k0 + sub * 32 >= N) break;            // wave-uniform: only padding left
+                f32x16 acc[QB];
+                mma_subtile(buf, sub, acc);
+                const int kbase = k0 + sub * 32 + 4 * half;
 #pragma unroll
                 for (int qb = 0; qb < QB; ++qb) {
                     if (tail) {
@@ -259,48 +301,88 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
                     }
                     l_run[qb] += sum;
                 }
-            } else {
-                // pass two: weights = 2^(c*s - bias), bias = c*m + log2(l)
+            }
+            if (j == n_tiles - 1) {
+                // lanes l and l+32 hold the two halves of each query's keys of this wave
 #pragma unroll
-                for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-                    for (int r4 = 0; r4 < 4; ++r4) {
-                        float p[4];
-#pragma unroll
-                        for (int i = 0; i < 4; ++i)
-                            p[i] = (ES == 4) ? fast_exp2(__builtin_fmaf(acc[qb][4 * r4 + i] - m_run[qb], c, -bias[qb]))
-                                             : fast_exp2(__builtin_fmaf(acc[qb][4 * r4 + i], c, -bias[qb]));
-                        stage_put4(qb, kt, r4, p[0], p[1], p[2], p[3]);
+                for (int qb = 0; qb < QB; ++qb) {
+                    const float mo = __shfl_xor(m_run[qb], 32, 64);
+                    const float lo = __shfl_xor(l_run[qb], 32, 64);
+                    const float mn = fmaxf(m_run[qb], mo);
+                    l_run[qb] = l_run[qb] * fast_exp2((m_run[qb] - mn) * c) + lo * fast_exp2((mo - mn) * c);
+                    m_run[qb] = mn;
+                    if (WK > 1 && half == 0) {
+                        stat_lds[(wave * QW + qb * 32 + l32) * 2] = mn;
+                        stat_lds[(wave * QW + qb * 32 + l32) * 2 + 1] = l_run[qb];
                     }
+                }
             }
-        }
-        if (SCORES || second) flush_stage(k0);
-
-        if (!SCORES && s == n_tiles - 1) {
-            // lanes l and l+32 hold the two halves of each query's keys: merge them
+            wait_vmem();                      // this wave's part of the next tile has landed in LDS
+            __syncthreads();
+        });
+        // the WK waves that share these queries each saw a different slice of the keys
 #pragma unroll
-            for (int qb = 0; qb < QB; ++qb) {
-                const float mo = __shfl_xor(m_run[qb], 32, 64);
-                const float lo = __shfl_xor(l_run[qb], 32, 64);
-                const float mn = fmaxf(m_run[qb], mo);
-                const float l = l_run[qb] * fast_exp2((m_run[qb] - mn) * c) + lo * fast_exp2((mo - mn) * c);
-                m_run[qb] = mn;
-                // bf16: bias = c*m + log2(l) folds max and normaliser into one constant;
-                // fp32: the max is subtracted separately, bias = log2(l)
-                bias[qb] = (ES == 4) ? fast_log2(l) : __builtin_fmaf(mn, c, fast_log2(l));
+        for (int qb = 0; qb < QB; ++qb) {
+            float mn = m_run[qb], l = l_run[qb];
+            if constexpr (WK > 1) {
+#pragma unroll
+                for (int o = 1; o < WK; ++o) {
+                    const int other = wq * WK + (wk + o) % WK;
+                    const float mo = stat_lds[(other * QW + qb * 32 + l32) * 2];
+                    const float lo = stat_lds[(other * QW + qb * 32 + l32) * 2 + 1];
+                    const float mx = fmaxf(mn, mo);
+                    l = l * fast_exp2((mn - mx) * c) + lo * fast_exp2((mo - mx) * c);
+                    mn = mx;
+                }
             }
+            m_run[qb] = mn;
+            // bf16: bias = c*m + log2(l) folds max and normaliser into one constant;
+            // fp32: the max is subtracted separately, bias = log2(l)
+            bias[qb] = (ES == 4) ? fast_log2(l) : __builtin_fmaf(mn, c, fast_log2(l));
         }
-
-        if (s + 1 < steps) k_commit(buf ^ 1);
-        __syncthreads();
     }
+
+    // ================= pass two (or the only pass of the score GEMM): compute, round, store ========
+    // pass one consumed n_tiles buffers, so tile 0 of this pass sits in buffer n_tiles & 1
+    for_tiles(SCORES ? 0 : (n_tiles & 1), n_tiles, [&](int j, auto buf) {
+        const int k0 = tile_at(j) * BN;
+        // stores of the previous tile first, then the next tile's loads: by the time this
+        // step ends and the wave waits for its loads, the stores have had a whole step to drain
+        if (j > 0) flush_stage(tile_at(j - 1) * BN + wk * SUBS * 32);
+        if (j + 1 < n_tiles) k_issue(tile_at(j + 1), IC<1 - decltype(buf)::value>{});
+#pragma unroll
+        for (int u = 0; u < SUBS; ++u) {
+            const int sub = wk * SUBS + u;
+            if (!FAST && k0 + sub * 32 >= N) break;                // wave-uniform: only padding left
+            f32x16 acc[QB];
+            mma_subtile(buf, sub, acc);
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    float p[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float sc = acc[qb][4 * r4 + i];
+                        if constexpr (SCORES) p[i] = sc * c;
+                        else if constexpr (ES == 4) p[i] = fast_exp2(__builtin_fmaf(sc - m_run[qb], c, -bias[qb]));
+                        else p[i] = fast_exp2(__builtin_fmaf(sc, c, -bias[qb]));   // 2^(c*s - c*m - log2 l)
+                    }
+                    stage_put4(qb, u, r4, p[0], p[1], p[2], p[3]);
+                }
+        }
+        wait_vmem();
+        __syncthreads();
+    });
+    flush_stage(tile_at(n_tiles - 1) * BN + wk * SUBS * 32);
 }
 
-template <typename T, int DB, int BN, int QB>
-hipError_t launch_shape(bool scores_only, const void* Q, const void* K, void* out, int64_t BH, int N, int d,
-                        float scale, hipStream_t stream)
+template <typename T, int DB, int QB, int WQ, int WK, int SUBS, bool FAST>
+hipError_t launch_variant(bool scores_only, const void* Q, const void* K, void* out, int64_t BH, int N, int d,
+                          float scale, hipStream_t stream)
 {
-    constexpr int BM = 128 * QB;
+    constexpr int BM = 32 * QB * WQ;
+    constexpr int threads = 64 * WQ * WK;
     const uint32_t strips = (uint32_t)((N + BM - 1) / BM);
     const uint64_t total = (uint64_t)BH * strips;
     const uint32_t grid = (uint32_t)((total + 7) / 8 * 8);
@@ -308,15 +390,26 @@ hipError_t launch_shape(bool scores_only, const void* Q, const void* K, void* ou
     const T* k = static_cast<const T*>(K);
     T* o = static_cast<T*>(out);
     if (scores_only) {
-        hipLaunchKernelGGL((qk_kernel<T, DB, BN, QB, true>), dim3(grid), dim3(256), 0, stream, q, k, o, N, d, scale, 0u,
-                           strips, (uint32_t)total);
+        hipLaunchKernelGGL((qk_kernel<T, DB, QB, WQ, WK, SUBS, true, FAST>), dim3(grid), dim3(threads), 0, stream, q, k,
+                           o, N, d, scale, 0u, strips, (uint32_t)total);
     } else {
         const float c = fabsf(scale) * kLog2e;
         const uint32_t flip = scale < 0.0f ? Mma<T>::kSignMask : 0u;
-        hipLaunchKernelGGL((qk_kernel<T, DB, BN, QB, false>), dim3(grid), dim3(256), 0, stream, q, k, o, N, d, c, flip,
-                           strips, (uint32_t)total);
+        hipLaunchKernelGGL((qk_kernel<T, DB, QB, WQ, WK, SUBS, false, FAST>), dim3(grid), dim3(threads), 0, stream, q,
+                           k, o, N, d, c, flip, strips, (uint32_t)total);
     }
     return hipGetLastError();
+}
+
+template <typename T, int DB, int QB, int WQ, int WK, int SUBS>
+hipError_t launch_shape(bool scores_only, const void* Q, const void* K, void* out, int64_t BH, int N, int d,
+                        float scale, hipStream_t stream)
+{
+    constexpr int BM = 32 * QB * WQ, BN = 32 * SUBS * WK;
+    // whole strips, whole K tiles, unpadded rows: the variant without masks and predicates
+    if (N % BM == 0 && N % BN == 0 && d * (int)sizeof(T) == DB)
+        return launch_variant<T, DB, QB, WQ, WK, SUBS, true>(scores_only, Q, K, out, BH, N, d, scale, stream);
+    return launch_variant<T, DB, QB, WQ, WK, SUBS, false>(scores_only, Q, K, out, BH, N, d, scale, stream);
 }
 
 template <typename T>
@@ -324,11 +417,21 @@ hipError_t launch_qk_t(bool scores_only, const void* Q, const void* K, void* out
                        float scale, hipStream_t stream)
 {
     const int row_bytes = d * (int)sizeof(T);
-    if (row_bytes <= 64) return launch_shape<T, 64, 64, 1>(scores_only, Q, K, out, BH, N, d, scale, stream);
-    if (row_bytes <= 128) return launch_shape<T, 128, 64, 1>(scores_only, Q, K, out, BH, N, d, scale, stream);
-    if (row_bytes <= 256) return launch_shape<T, 256, 64, 1>(scores_only, Q, K, out, BH, N, d, scale, stream);
-    if (row_bytes <= 512) return launch_shape<T, 512, 32, 1>(scores_only, Q, K, out, BH, N, d, scale, stream);
-    if constexpr (sizeof(T) == 4) return launch_shape<T, 1024, 32, 1>(scores_only, Q, K, out, BH, N, d, scale, stream);
+    constexpr int QB = sizeof(T) == 2 ? 2 : 1;   // fp32 stages twice the bytes per key: half the queries per wave
+    // wide strips (4 waves along the queries) when that still gives every compute unit work
+    const bool big = BH * ((N + 128 * QB - 1) / (128 * QB)) >= 200;
+    if (row_bytes <= 64)
+        return big ? launch_shape<T, 64, QB, 4, 2, 2>(scores_only, Q, K, out, BH, N, d, scale, stream)
+                   : launch_shape<T, 64, QB, 1, 2, 2>(scores_only, Q, K, out, BH, N, d, scale, stream);
+    if (row_bytes <= 128)
+        return big ? launch_shape<T, 128, QB, 4, 2, 2>(scores_only, Q, K, out, BH, N, d, scale, stream)
+                   : launch_shape<T, 128, QB, 1, 2, 2>(scores_only, Q, K, out, BH, N, d, scale, stream);
+    if (row_bytes <= 256)
+        return big ? launch_shape<T, 256, QB, 4, 2, 2>(scores_only, Q, K, out, BH, N, d, scale, stream)
+                   : launch_shape<T, 256, QB, 1, 2, 2>(scores_only, Q, K, out, BH, N, d, scale, stream);
+    if (row_bytes <= 512) return launch_shape<T, 512, 1, 4, 2, 1>(scores_only, Q, K, out, BH, N, d, scale, stream);
+    if constexpr (sizeof(T) == 4)
+        return launch_shape<T, 1024, 1, 4, 1, 1>(scores_only, Q, K, out, BH, N, d, scale, stream);
     return hipErrorInvalidValue;   // unreachable: d <= 256 bounds row_bytes
 }
 
