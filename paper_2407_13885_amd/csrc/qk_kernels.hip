@@ -60,6 +60,12 @@ template <> struct Mma<float> {
 
 // vmcnt(0) with the other counters left alone (gfx9 encoding of s_waitcnt)
 __device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+// vmcnt(N): wait until at most the N youngest vector-memory operations are outstanding
+template <int N> __device__ __forceinline__ void wait_vmem_le()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
 
 // 16 bytes per lane from global memory straight into LDS (lane i lands at dst + 16*i;
 // dst is wave-uniform).  The __restrict__ parameters give the transfer an alias scope of
@@ -72,13 +78,22 @@ __device__ __forceinline__ void dma16(const char* __restrict__ src, char* __rest
 
 template <int I> struct IC { static constexpr int value = I; };
 
-// Calls body(tile, IC<buffer>) for tile = 0 .. n-1 with the LDS buffer alternating from
-// `first`; the buffer is a compile-time constant inside body.
-template <typename Body>
-__device__ __forceinline__ void for_tiles(int first, int n, Body&& body)
+// f(IC<0>{}), f(IC<1>{}), ... f(IC<N-1>{})
+template <int N, typename F> __device__ __forceinline__ void static_for(F&& f)
 {
-    int t = 0;
-    if (first == 1 && n > 0) { body(t, IC<1>{}); ++t; }
+    if constexpr (N > 0) {
+        static_for<N - 1>(f);
+        f(IC<N - 1>{});
+    }
+}
+
+// Calls body(t, IC<buffer>) for t = first .. n-1 with the LDS buffer alternating from
+// `buf_first`; the buffer is a compile-time constant inside body.
+template <typename Body>
+__device__ __forceinline__ void for_tiles(int first, int buf_first, int n, Body&& body)
+{
+    int t = first;
+    if (buf_first == 1 && t < n) { body(t, IC<1>{}); ++t; }
     for (; t + 1 < n; t += 2) {
         body(t, IC<0>{});
         body(t + 1, IC<1>{});
@@ -178,8 +193,8 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
     // sit a whole row pitch apart and land on the same few memory channels; the
     // stagger spreads the store stream over all of them.
     const int rot = (int)((logical * 7u) % (uint32_t)n_tiles);
-    auto tile_at = [&](int j) { const int t = j + rot; return t >= n_tiles ? t - n_tiles : t; };
-    auto k_issue = [&](int tile, auto bufc) {
+    auto tile_at = [&](int j) __attribute__((always_inline)) { const int t = j + rot; return t >= n_tiles ? t - n_tiles : t; };
+    auto k_issue = [&](int tile, auto bufc) __attribute__((always_inline)) {
         char* const k_buf = decltype(bufc)::value == 0 ? k_lds0 : k_lds1;
         const int k0 = tile * BN;
         const char* tile_base = Kh + (int64_t)k0 * row_bytes;
@@ -217,7 +232,7 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
     // move the wave's staged QW x (32*SUBS) block to global memory, 16 bytes per lane
     const bool vec_ok = FAST || (N % EPC) == 0;
     T* const out_lane = out_h + (int64_t)(qw0 + lane / CPS) * N + (lane % CPS) * EPC;
-    auto flush_stage = [&](int kseg0) {
+    auto flush_stage = [&](int kseg0) __attribute__((always_inline)) {
 #pragma unroll
         for (int it = 0; it < QW / RPI; ++it) {
             const int row = it * RPI + lane / CPS;
@@ -241,7 +256,7 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
             }
         }
     };
-    auto stage_put4 = [&](int qb, int u, int r4, float v0, float v1, float v2, float v3) {
+    auto stage_put4 = [&](int qb, int u, int r4, float v0, float v1, float v2, float v3) __attribute__((always_inline)) {
         char* p = stage + (qb * 32 + l32) * ST_PITCH + (u * 32 + 8 * r4 + 4 * half) * ES;
         if constexpr (ES == 2) {
             u32x2 w = {pack_bf16x2(v0, v1), pack_bf16x2(v2, v3)};
@@ -256,71 +271,124 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) { m_run[qb] = kNegBig; l_run[qb] = 0.0f; bias[qb] = 0.0f; }
 
+    // pass one on the scores of one 32-key sub-tile: running maximum and sum of
+    // exponentials (Eq. 1), kept per lane; kbase = first key of this lane's first run
+    auto fold_stats = [&](f32x16 (&acc)[QB], int kbase, bool tail) {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            if (tail) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (kbase + 8 * (r / 4) + (r % 4) >= N) acc[qb][r] = kNegBig;
+            }
+            float tm = max3(acc[qb][0], acc[qb][1], acc[qb][2]);
+#pragma unroll
+            for (int r = 3; r < 15; r += 2) tm = max3(tm, acc[qb][r], acc[qb][r + 1]);
+            tm = fmaxf(tm, acc[qb][15]);
+            const float mn = fmaxf(m_run[qb], tm);
+            l_run[qb] *= fast_exp2((m_run[qb] - mn) * c);
+            m_run[qb] = mn;
+            const float mb = mn * c;
+            float sum = 0.0f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                // fp32 results are held to an absolute bound: subtract first so that a
+                // large common offset cancels exactly
+                float e = (ES == 4) ? fast_exp2((acc[qb][r] - mn) * c) : fast_exp2(__builtin_fmaf(acc[qb][r], c, -mb));
+                if (tail && kbase + 8 * (r / 4) + (r % 4) >= N) e = 0.0f;
+                sum += e;
+            }
+            l_run[qb] += sum;
+        }
+    };
+    // pass two (or the score GEMM) on one sub-tile: final values, rounded, into the staging rows
+    auto emit = [&](f32x16 (&acc)[QB], int u) {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                float p[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float sc = acc[qb][4 * r4 + i];
+                    if constexpr (SCORES) p[i] = sc * c;
+                    else if constexpr (ES == 4) p[i] = fast_exp2(__builtin_fmaf(sc - m_run[qb], c, -bias[qb]));
+                    else p[i] = fast_exp2(__builtin_fmaf(sc, c, -bias[qb]));   // 2^(c*s - c*m - log2 l)
+                }
+                stage_put4(qb, u, r4, p[0], p[1], p[2], p[3]);
+            }
+    };
+
+    // ---- the sweep -------------------------------------------------------------------------
+    // The K tiles of both passes form one sequence s = 0 .. S-1 (tile_at(s mod n_tiles),
+    // LDS buffer s & 1).  A wave always has two things in flight: the MFMAs of its next
+    // sub-tile and the VALU work on the scores of the previous one (two accumulator sets),
+    // also across the workgroup barrier that ends a tile -- a wave that issued only
+    // MFMAs, or only VALU work, between two barriers would leave the other unit idle.
+    //   body(s):  [store the rows staged during s-1]
+    //             for u < SUBS-1:  MFMA(s, u+1)  ||  VALU(s, u)
+    //             wait for the DMA of tile s+1, barrier, start the DMA of tile s+2
+    //             MFMA(s+1, 0)  ||  VALU(s, SUBS-1)
+    constexpr int NST = QW / RPI;             // store instructions per flush
+    f32x16 acc_a[QB], acc_b[QB];              // accumulator set of sub-tile u of buffer b: (b*SUBS + u) & 1
+    auto acc_of = [&](auto slotc) __attribute__((always_inline)) -> f32x16 (&)[QB] {
+        if constexpr ((decltype(slotc)::value & 1) == 0) return acc_a; else return acc_b;
+    };
+
     k_issue(tile_at(0), IC<0>{});
     wait_vmem();
     __syncthreads();
+    k_issue(tile_at(1 % n_tiles), IC<1>{});
+    mma_subtile(IC<0>{}, wk * SUBS, acc_of(IC<0>{}));
+
+    // Nothing in a body depends on whether a next tile exists: past the end of the sequence
+    // the extra DMA re-reads a valid tile and the extra MFMAs chew on stale LDS, both
+    // unused -- a branch there would split the block the scheduler interleaves.
+    auto body = [&](int j, auto bufc, auto writec, auto flushc) __attribute__((always_inline)) {
+        constexpr int B = decltype(bufc)::value;
+        constexpr bool WRITE = decltype(writec)::value != 0;   // this tile's results go to memory
+        constexpr bool FLUSH = decltype(flushc)::value != 0;   // the previous tile's are still staged
+        const int k0 = tile_at(j) * BN;
+        const bool tail = !FAST && k0 + BN > N;
+        if constexpr (FLUSH) flush_stage(tile_at(j - 1) * BN + wk * SUBS * 32);
+        static_for<SUBS - 1>([&](auto uc) __attribute__((always_inline)) {
+            constexpr int u = decltype(uc)::value;
+            mma_subtile(bufc, wk * SUBS + u + 1, acc_of(IC<B * SUBS + u + 1>{}));
+            if constexpr (WRITE) emit(acc_of(IC<B * SUBS + u>{}), u);
+            else fold_stats(acc_of(IC<B * SUBS + u>{}), k0 + (wk * SUBS + u) * 32 + 4 * half, tail);
+        });
+        // The DMA of tile s+1 is older than this body's stores and memory operations
+        // retire in order, so the wait can leave the NST stores in flight.
+        if constexpr (FAST && FLUSH) wait_vmem_le<NST>(); else wait_vmem();
+        __syncthreads();
+        k_issue(tile_at(j + 2 < n_tiles ? j + 2 : j + 2 - n_tiles), bufc);   // this tile's buffer is free now
+        // Pin the transfer here: left alone, the scheduler sinks it to the end of the block,
+        // right in front of the wait that needs it, and its whole latency is exposed.
+        __builtin_amdgcn_sched_barrier(0);
+        mma_subtile(IC<1 - B>{}, wk * SUBS, acc_of(IC<(1 - B) * SUBS>{}));
+        if constexpr (WRITE) emit(acc_of(IC<B * SUBS + SUBS - 1>{}), SUBS - 1);
+        else fold_stats(acc_of(IC<B * SUBS + SUBS - 1>{}), k0 + (wk * SUBS + SUBS - 1) * 32 + 4 * half, tail);
+    };
 
     if constexpr (!SCORES) {
-        // ================= pass one: running row maximum and sum of exponentials (Eq. 1) =========
-        for_tiles(0, n_tiles, [&](int j, auto buf) {
-            const int tile = tile_at(j);
-            const int k0 = tile * BN;
-            const bool tail = !FAST && k0 + BN > N;
-            k_issue(tile_at(j + 1 < n_tiles ? j + 1 : 0), IC<1 - decltype(buf)::value>{});   // pass two starts over
+        // ================= pass one =================================================================
+        for_tiles(0, 0, n_tiles, [&](int j, auto bufc) __attribute__((always_inline)) { body(j, bufc, IC<0>{}, IC<0>{}); });
+
+        // lanes l and l+32 hold the two halves of each query's keys of this wave; the WK
+        // waves that share these queries each saw a different slice of every tile
 #pragma unroll
-            for (int u = 0; u < SUBS; ++u) {
-                const int sub = wk * SUBS + u;
-                if (!FAST && k0 + sub * 32 >= N) break;            // wave-uniform: only padding left
-                f32x16 acc[QB];
-                mma_subtile(buf, sub, acc);
-                const int kbase = k0 + sub * 32 + 4 * half;
-#pragma unroll
-                for (int qb = 0; qb < QB; ++qb) {
-                    if (tail) {
-#pragma unroll
-                        for (int r = 0; r < 16; ++r)
-                            if (kbase + 8 * (r / 4) + (r % 4) >= N) acc[qb][r] = kNegBig;
-                    }
-                    float tm = max3(acc[qb][0], acc[qb][1], acc[qb][2]);
-#pragma unroll
-                    for (int r = 3; r < 15; r += 2) tm = max3(tm, acc[qb][r], acc[qb][r + 1]);
-                    tm = fmaxf(tm, acc[qb][15]);
-                    const float mn = fmaxf(m_run[qb], tm);
-                    l_run[qb] *= fast_exp2((m_run[qb] - mn) * c);
-                    m_run[qb] = mn;
-                    const float mb = mn * c;
-                    float sum = 0.0f;
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        // fp32 results are held to an absolute bound: subtract first so
-                        // that a large common offset cancels exactly
-                        float e = (ES == 4) ? fast_exp2((acc[qb][r] - mn) * c)
-                                            : fast_exp2(__builtin_fmaf(acc[qb][r], c, -mb));
-                        if (tail && kbase + 8 * (r / 4) + (r % 4) >= N) e = 0.0f;
-                        sum += e;
-                    }
-                    l_run[qb] += sum;
-                }
+        for (int qb = 0; qb < QB; ++qb) {
+            const float mo = __shfl_xor(m_run[qb], 32, 64);
+            const float lo = __shfl_xor(l_run[qb], 32, 64);
+            const float mn = fmaxf(m_run[qb], mo);
+            l_run[qb] = l_run[qb] * fast_exp2((m_run[qb] - mn) * c) + lo * fast_exp2((mo - mn) * c);
+            m_run[qb] = mn;
+            if (WK > 1 && half == 0) {
+                stat_lds[(wave * QW + qb * 32 + l32) * 2] = mn;
+                stat_lds[(wave * QW + qb * 32 + l32) * 2 + 1] = l_run[qb];
             }
-            if (j == n_tiles - 1) {
-                // lanes l and l+32 hold the two halves of each query's keys of this wave
-#pragma unroll
-                for (int qb = 0; qb < QB; ++qb) {
-                    const float mo = __shfl_xor(m_run[qb], 32, 64);
-                    const float lo = __shfl_xor(l_run[qb], 32, 64);
-                    const float mn = fmaxf(m_run[qb], mo);
-                    l_run[qb] = l_run[qb] * fast_exp2((m_run[qb] - mn) * c) + lo * fast_exp2((mo - mn) * c);
-                    m_run[qb] = mn;
-                    if (WK > 1 && half == 0) {
-                        stat_lds[(wave * QW + qb * 32 + l32) * 2] = mn;
-                        stat_lds[(wave * QW + qb * 32 + l32) * 2 + 1] = l_run[qb];
-                    }
-                }
-            }
-            wait_vmem();                      // this wave's part of the next tile has landed in LDS
-            __syncthreads();
-        });
-        // the WK waves that share these queries each saw a different slice of the keys
+        }
+        if constexpr (WK > 1) __syncthreads();
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
             float mn = m_run[qb], l = l_run[qb];
@@ -343,37 +411,11 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
     }
 
     // ================= pass two (or the only pass of the score GEMM): compute, round, store ========
-    // pass one consumed n_tiles buffers, so tile 0 of this pass sits in buffer n_tiles & 1
-    for_tiles(SCORES ? 0 : (n_tiles & 1), n_tiles, [&](int j, auto buf) {
-        const int k0 = tile_at(j) * BN;
-        // stores of the previous tile first, then the next tile's loads: by the time this
-        // step ends and the wave waits for its loads, the stores have had a whole step to drain
-        if (j > 0) flush_stage(tile_at(j - 1) * BN + wk * SUBS * 32);
-        if (j + 1 < n_tiles) k_issue(tile_at(j + 1), IC<1 - decltype(buf)::value>{});
-#pragma unroll
-        for (int u = 0; u < SUBS; ++u) {
-            const int sub = wk * SUBS + u;
-            if (!FAST && k0 + sub * 32 >= N) break;                // wave-uniform: only padding left
-            f32x16 acc[QB];
-            mma_subtile(buf, sub, acc);
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-                for (int r4 = 0; r4 < 4; ++r4) {
-                    float p[4];
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const float sc = acc[qb][4 * r4 + i];
-                        if constexpr (SCORES) p[i] = sc * c;
-                        else if constexpr (ES == 4) p[i] = fast_exp2(__builtin_fmaf(sc - m_run[qb], c, -bias[qb]));
-                        else p[i] = fast_exp2(__builtin_fmaf(sc, c, -bias[qb]));   // 2^(c*s - c*m - log2 l)
-                    }
-                    stage_put4(qb, u, r4, p[0], p[1], p[2], p[3]);
-                }
-        }
-        wait_vmem();
-        __syncthreads();
-    });
+    // pass one consumed n_tiles buffers, so the first tile of this pass sits in buffer n_tiles & 1
+    const int b0 = SCORES ? 0 : (n_tiles & 1);
+    if (b0 == 0) body(0, IC<0>{}, IC<1>{}, IC<0>{}); else body(0, IC<1>{}, IC<1>{}, IC<0>{});
+    for_tiles(1, b0 ^ 1, n_tiles, [&](int j, auto bufc) __attribute__((always_inline)) { body(j, bufc, IC<1>{}, IC<1>{}); });
+    wait_vmem();
     flush_stage(tile_at(n_tiles - 1) * BN + wk * SUBS * 32);
 }
 
