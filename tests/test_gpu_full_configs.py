@@ -1,0 +1,85 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration bench.py times.
+
+c2 and c3 are compared with the oracle on every element.  c4 and c5 are compared on
+sampled query rows (first / last rows of strips, strip interiors, seeded random rows of
+every head), which the oracle computes one by one, and on a property that holds at any
+size and needs no oracle: every row of P sums to 1."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2407_13885_amd import workloads as wl
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _gpu():
+    gu.require_gpu()
+
+
+def _row_sums_ok(P, tol):
+    worst = 0.0
+    for b in range(P.shape[0]):
+        for h in range(P.shape[1]):
+            worst = max(worst, float((P[b, h].float().sum(-1) - 1.0).abs().max().item()))
+    assert worst <= tol, f"row sum off by {worst:.3e}"
+
+
+def _sample_rows(N, seed, n_random=24):
+    fixed = [0, 1, 31, 32, 63, 64, 127, 128, 255, 256, N // 2 - 1, N // 2, N - 257, N - 256, N - 2, N - 1]
+    rnd = np.random.default_rng(seed).integers(0, N, size=n_random).tolist()
+    return sorted({r for r in fixed + rnd if 0 <= r < N})
+
+
+def test_c2_full_softmax_bf16():
+    s = wl.c2()
+    P = gu.run_softmax(gu.to_dev(s.S, "bf16"), s.rows, s.cols, "bf16", guard=4096)
+    for r0 in range(0, s.rows, 4096):           # the oracle's fp64 output, 64 MiB at a time
+        r1 = min(r0 + 4096, s.rows)
+        gu.check_weights(gu.to_f64(P[r0:r1]), oracle.softmax(s.S, "bf16", rows=(r0, r1)), "bf16", f"c2 rows {r0}..{r1}")
+
+
+def test_c3_full_fused_bf16():
+    x = wl.c3()
+    P = gu.run_fused(x, guard=8192)
+    for b in range(x.B):
+        for h in range(x.H):
+            ref = oracle.attention_weights(x.Q[b, h], x.K[b, h], "bf16", x.scale)
+            gu.check_weights(gu.to_f64(P[b, h]), ref, "bf16", f"c3 head ({b},{h})")
+
+
+@pytest.mark.parametrize("name", ["c4", "c5"])
+def test_large_fused_sampled_rows_and_row_sums(name):
+    x = wl.CONFIGS[name]()
+    P = gu.run_fused(x, guard=8192)
+    _row_sums_ok(P, gu.ROWSUM_BF16)
+    assert bool(torch.isfinite(P.view(-1)[:: 4099].float()).all().item())
+    for b in range(x.B):
+        for h in range(x.H):
+            rows = _sample_rows(x.N, seed=1000 * b + h)
+            got = gu.to_f64(P[b, h][rows])
+            ref = np.concatenate([oracle.attention_weights(x.Q[b, h], x.K[b, h], "bf16", x.scale, rows=(r, r + 1))
+                                  for r in rows])
+            gu.check_weights(got, ref, "bf16", f"{name} head ({b},{h}) sampled rows")
+
+
+def test_c4_unfused_pair_full_size():
+    """The unfused pair at the paper's fused size: score GEMM checked on sampled rows,
+    softmax checked against the oracle softmax of the scores actually produced."""
+    x = wl.c4()
+    S = gu.run_scores(x)
+    Sv = S.view(x.H * x.N, x.N)
+    Pm = gu.run_softmax(Sv, x.H * x.N, x.N, "bf16")
+    _row_sums_ok(Pm.view(1, x.H, x.N, x.N), gu.ROWSUM_BF16)
+    for h in (0, 7, 15):
+        rows = _sample_rows(x.N, seed=77 + h, n_random=8)
+        ref_s = np.concatenate([oracle.scores(x.Q[0, h], x.K[0, h], "bf16", x.scale, rows=(r, r + 1)) for r in rows])
+        got_s = gu.to_f64(S[0, h][rows])
+        assert (np.abs(got_s - ref_s) <= 2.0 ** -8 * np.abs(ref_s) + 1e-4).all(), f"scores head {h}"
+        s_bits = S[0, h][rows].cpu().view(torch.int16).numpy().view(np.uint16)
+        gu.check_weights(gu.to_f64(Pm.view(x.H, x.N, x.N)[h][rows]), oracle.softmax(s_bits, "bf16"), "bf16",
+                         f"unfused softmax head {h}")
