@@ -198,6 +198,19 @@ def cpu_baseline_softmax(x, rows=8192):
     }
 
 
+def measured_traffic(workload: str, call: str):
+    """HBM bytes per launch from the committed rocprofv3 counter summary (profiles/hbm_traffic.txt), or None."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) >= 5 and f[0] == workload and f[1] == call:
+                return int(float(f[4]))
+    except OSError:
+        pass
+    return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -207,6 +220,9 @@ def main() -> int:
                     help="configuration reported at the top level of the JSON line")
     ap.add_argument("--only", action="store_true", help="measure the headline workload only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also launch one plain elementwise copy of 1 GiB (read 1 GiB, write 1 GiB): the known-size "
+                         "kernel that rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -223,6 +239,14 @@ def main() -> int:
         return 2
     attnw.load_library()   # raises if libattnw.so is missing: there is no fallback
     torch.cuda.set_device(0)
+
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)      # one elementwise kernel: 2^30 bytes in, 2^30 bytes out
+        torch.cuda.synchronize()
+        del src, dst
 
     order = ["c2", "c3", "c4", "c5"]
     todo = [args.workload] if args.only else order
@@ -257,7 +281,8 @@ def main() -> int:
         "config": {"workload": f"{args.workload}: {head['call']} {json.dumps(head['shape'])}",
                    "generator": wl.GENERATOR_ID, "buffer_sets": head["buffer_sets"]},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": head["hbm_GBps"], "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": head["hbm_frac_of_peak"], "traffic": None},
+                     "unit": "GB/s", "frac": head["hbm_frac_of_peak"],
+                     "traffic": measured_traffic(args.workload, head["call"])},
         "cpu_baseline": cpu,
         "fused_vs_unfused_speedup": {k: v.get("fused_vs_unfused_speedup") for k, v in results.items()
                                      if "fused_vs_unfused_speedup" in v},
