@@ -13,7 +13,11 @@ dedicated softmax on c2, the fused kernel on c3 and c5, and the unfused pair
 Timing: W untimed calls, then exactly K calls bracketed by a device
 synchronisation on both sides (wall clock -> ``ms_per_step`` and ``value``) and
 by HIP events recorded on the stream the kernels are launched on (-> the
-average launch duration used for the roofline).  Working sets smaller than the
+average launch duration used for the roofline).  Without --steps / --warmup, W
+and K are sized per timed section from a three-call pilot so that the warm-up
+lasts about 0.4 s and the timed region about 0.3 s: the shader clock starts
+low on an idle GPU and takes a few hundred milliseconds of load to settle, and
+a 5 + 20 call measurement of a 0.2 ms kernel sits entirely inside that ramp.  Working sets smaller than the
 256 MB last-level cache are rotated through distinct buffers (> 1 GiB in total)
 so that no call finds its data on chip.
 
@@ -47,10 +51,29 @@ def _dev(a, dtype):
     return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda().view(torch.bfloat16)
 
 
+WARM_MS = 400.0   # default warm-up per timed section: the shader clock needs this long under load to settle
+TIMED_MS = 300.0  # default length of a timed section
+
+
 def _time_calls(call, n_sets, steps, warmup):
-    """call(i) launches one step on buffer set i % n_sets.  Returns (wall ms/step, event ms/step)."""
+    """call(i) launches one step on buffer set i % n_sets.  ``steps`` / ``warmup`` None: sized from a
+    short pilot run so that the warm-up covers WARM_MS and the timed region TIMED_MS.
+    Returns (wall ms/step, event ms/step, steps, warmup)."""
     import torch
     stream = torch.cuda.current_stream()
+    if steps is None or warmup is None:
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        call(0)
+        e0.record(stream)
+        for i in range(3):
+            call(i % n_sets)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        pilot = max(e0.elapsed_time(e1) / 3, 1e-3)
+        if warmup is None:
+            warmup = min(max(int(WARM_MS / pilot), 5), 50000)
+        if steps is None:
+            steps = min(max(int(TIMED_MS / pilot), 20), 50000)
     for i in range(warmup):
         call(i % n_sets)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -62,7 +85,7 @@ def _time_calls(call, n_sets, steps, warmup):
     e1.record(stream)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
+    return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps, steps, warmup
 
 
 def _n_sets(set_bytes):
@@ -71,10 +94,12 @@ def _n_sets(set_bytes):
     return int(math.ceil(ROTATE_BYTES / set_bytes))
 
 
-def _record(name, what, elements, alg_bytes, wall_ms, ev_ms, n_sets):
+def _record(name, what, elements, alg_bytes, timing, n_sets):
+    wall_ms, ev_ms, steps, warmup = timing
     gbs = alg_bytes / (ev_ms * 1e-3) * 1e-9
     return {
         "workload": name, "call": what, "elements": elements, "algorithmic_bytes": alg_bytes,
+        "steps": steps, "warmup": warmup,
         "ms_per_step": round(wall_ms, 5), "kernel_ms": round(ev_ms, 5),
         "elements_per_s": elements / (wall_ms * 1e-3),
         "hbm_GBps": round(gbs, 1), "hbm_frac_of_peak": round(gbs / HBM_PEAK_GBS, 4), "buffer_sets": n_sets,
@@ -95,9 +120,9 @@ def bench_softmax(cfg, steps, warmup):
     def call(i):
         attnw.attnw_softmax(S[i], P[i], x.rows, x.cols, dt, stream)
 
-    wall, ev = _time_calls(call, n_sets, steps, warmup)
+    timing = _time_calls(call, n_sets, steps, warmup)
     rs = float((P[0].float().sum(-1) - 1.0).abs().max().item())
-    rec = _record(x.name, "attnw_softmax", x.elements, x.algorithmic_bytes, wall, ev, n_sets)
+    rec = _record(x.name, "attnw_softmax", x.elements, x.algorithmic_bytes, timing, n_sets)
     rec["max_row_sum_error"] = rs
     rec["shape"] = {"rows": x.rows, "cols": x.cols, "dtype": x.dtype}
     return rec, x
@@ -120,8 +145,9 @@ def bench_fused(cfg, steps, warmup, with_unfused=True):
     def call(i):
         attnw.attnw_fused(Q, K, P[i], x.B, x.H, x.N, x.d, scale, dt, stream)
 
-    wall, ev = _time_calls(call, n_sets, steps, warmup)
-    rec = _record(x.name, "attnw_fused", x.elements, x.algorithmic_bytes, wall, ev, n_sets)
+    timing = _time_calls(call, n_sets, steps, warmup)
+    ev = timing[1]
+    rec = _record(x.name, "attnw_fused", x.elements, x.algorithmic_bytes, timing, n_sets)
     rec["shape"] = {"B": x.B, "H": x.H, "N": x.N, "d": x.d, "dtype": x.dtype}
     rec["mfma_TFLOPs_two_pass"] = round(2 * 2.0 * x.elements * x.d / (ev * 1e-3) * 1e-12, 1)
     # row sums of every row (a property that needs no oracle)
@@ -146,9 +172,9 @@ def bench_fused(cfg, steps, warmup, with_unfused=True):
             call_gemm(i)
             call_sm(i)
 
-        wall_p, ev_p = _time_calls(call_pair, n_sets, steps, warmup)
-        _, ev_g = _time_calls(call_gemm, n_sets, steps, warmup)
-        _, ev_s = _time_calls(call_sm, n_sets, steps, warmup)
+        wall_p, ev_p, _, _ = _time_calls(call_pair, n_sets, steps, warmup)
+        _, ev_g, _, _ = _time_calls(call_gemm, n_sets, steps, warmup)
+        _, ev_s, _, _ = _time_calls(call_sm, n_sets, steps, warmup)
         unf_bytes = x.algorithmic_bytes + 2 * out_bytes      # + write S, read S
         rec["unfused"] = {
             "ms_per_step": round(wall_p, 5), "kernel_ms": round(ev_p, 5),
@@ -214,8 +240,11 @@ def measured_traffic(workload: str, call: str):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=None,
+                    help="timed calls per section (default: as many as fill about 0.3 s)")
+    ap.add_argument("--warmup", type=int, default=None,
+                    help="untimed calls before every timed section (default: as many as fill about 0.4 s, "
+                         "the time the shader clock takes to settle under load)")
     ap.add_argument("--workload", default="c4", choices=["c2", "c3", "c4", "c5"],
                     help="configuration reported at the top level of the JSON line")
     ap.add_argument("--only", action="store_true", help="measure the headline workload only")
@@ -267,12 +296,12 @@ def main() -> int:
         print("[bench] cpu_baseline (oracle on host cores) ...", file=sys.stderr, flush=True)
         cpu = cpu_baseline_softmax(x) if args.workload == "c2" else cpu_baseline_fused(x)
 
-    dominant = "softmax_rows_kernel" if args.workload == "c2" else "qk_kernel"
+    dominant = "softmax_rows_kernel" if args.workload == "c2" else "qk_rounds_kernel"
     line = {
         "metric": METRIC,
         "value": head["elements_per_s"],
         "unit": "elements/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "n_gpus": 1, "steps": head["steps"], "warmup": head["warmup"],
         "ms_per_step": head["ms_per_step"],
         "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None,

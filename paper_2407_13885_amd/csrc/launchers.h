@@ -15,4 +15,10 @@ hipError_t launch_softmax(DType dt, const void* S, void* P, int64_t rows, int64_
 hipError_t launch_qk(DType dt, bool scores_only, const void* Q, const void* K, void* out,
                      int64_t BH, int64_t N, int64_t d, float scale, hipStream_t stream);
 
+// Fused attention weights, bf16, by the round-based kernel (statistics of one strip gathered while the
+// weights of the previous one are written).  Only for the shapes qk_rounds_supported() accepts.
+bool qk_rounds_supported(int64_t BH, int64_t N, int64_t d);
+hipError_t launch_qk_rounds(const void* Q, const void* K, void* out, int64_t BH, int64_t N, int64_t d, float scale,
+                            hipStream_t stream);
+
 }  // namespace attnw

@@ -26,6 +26,9 @@
 #include "launchers.h"
 #include "qk_common.h"
 
+#include <cstdlib>
+#include <cstring>
+
 namespace attnw {
 namespace {
 
@@ -411,6 +414,11 @@ hipError_t launch_qk(DType dt, bool scores_only, const void* Q, const void* K, v
                      int64_t BH, int64_t N, int64_t d, float scale, hipStream_t stream)
 {
     if (dt == DType::F32) return launch_qk_t<float>(scores_only, Q, K, out, BH, (int)N, (int)d, scale, stream);
+    // ATTNW_FUSED_KERNEL=twopass keeps bf16 problems on the two-pass kernel above (tests compare the two)
+    if (!scores_only && qk_rounds_supported(BH, N, d)) {
+        const char* force = getenv("ATTNW_FUSED_KERNEL");
+        if (!(force && strcmp(force, "twopass") == 0)) return launch_qk_rounds(Q, K, out, BH, N, d, scale, stream);
+    }
     return launch_qk_t<uint16_t>(scores_only, Q, K, out, BH, (int)N, (int)d, scale, stream);
 }
 

@@ -61,6 +61,26 @@ def test_fused_bf16_small(B, H, N, d):
     gu.check_weights(gu.to_f64(P), _oracle_heads(x), "bf16", f"fused bf16 {B}x{H}x{N}x{d}")
 
 
+# ---- fused bf16, shapes served by the round-based kernel (N a multiple of 256, d = 64 or 128) ---
+# 600 strips over 256 workgroups: strip lists that cross head boundaries; 20 strips: workgroups
+# with one strip (a statistics round followed directly by a weights round) and idle ones;
+# one head with many strips: long lists inside one head.
+
+@pytest.mark.parametrize("B,H,N,d", [(3, 100, 256, 64), (1, 5, 512, 128), (1, 1, 2048, 128), (2, 2, 1536, 64),
+                                     (1, 130, 256, 128)])
+def test_fused_bf16_round_kernel_shapes(B, H, N, d):
+    x = wl.fused_inputs("t", "bf16", B, H, N, d, seed=700 + H + N + d)
+    P = gu.run_fused(x, guard=8192)
+    gu.check_weights(gu.to_f64(P), _oracle_heads(x), "bf16", f"round kernel {B}x{H}x{N}x{d}")
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_fused_bf16_round_kernel_negative_scale_and_sharp_rows(d):
+    x = wl.fused_inputs("t", "bf16", 1, 3, 512, d, seed=31 + d, scale=-1.0 / math.sqrt(d), row_factor=(0.5, 3.0))
+    P = gu.run_fused(x, guard=4096)
+    gu.check_weights(gu.to_f64(P), _oracle_heads(x), "bf16", f"round kernel, negative scale, d={d}")
+
+
 @pytest.mark.parametrize("N", [1, 2, 3, 4, 7, 17, 31, 33, 100, 129, 257])
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_fused_ragged_n(N, dtype):
