@@ -249,6 +249,7 @@ def main() -> int:
                     help="configuration reported at the top level of the JSON line")
     ap.add_argument("--only", action="store_true", help="measure the headline workload only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-unfused", action="store_true", help="skip the unfused pair (score GEMM, then softmax)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch one plain elementwise copy of 1 GiB (read 1 GiB, write 1 GiB): the known-size "
                          "kernel that rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -285,7 +286,8 @@ def main() -> int:
         if name == "c2":
             results[name], inputs[name] = bench_softmax(wl.c2, args.steps, args.warmup)
         else:
-            results[name], inputs[name] = bench_fused(wl.CONFIGS[name], args.steps, args.warmup)
+            results[name], inputs[name] = bench_fused(wl.CONFIGS[name], args.steps, args.warmup,
+                                                      with_unfused=not args.no_unfused)
         if name != args.workload:
             inputs.pop(name)
 
