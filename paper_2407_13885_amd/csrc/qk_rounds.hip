@@ -427,7 +427,16 @@ bool qk_rounds_supported(int64_t BH, int64_t N, int64_t d)
 hipError_t launch_qk_rounds(const void* Q, const void* K, void* out, int64_t BH, int64_t N, int64_t d, float scale,
                             hipStream_t stream)
 {
-    if (d == 64) return launch_rounds<128, 4, 2>(Q, K, out, BH, (int)N, scale, stream);
+    if (d == 64) {
+        // Few strips per workgroup: lists of 1 or 2 strips leave some workgroups with twice the work of
+        // others and make the statistics-only and weights-only rounds a large share.  Strips of 64 queries
+        // (2 x 4 waves, 256-key tiles) double the list lengths; K traffic per element doubles, which small
+        // problems can afford.  (d = 128 has no LDS for 256-key tiles.)
+        const int64_t strips128 = BH * (N / 128);
+        if (strips128 < 4 * (int64_t)compute_units() && (N % 512) == 0)
+            return launch_rounds<128, 2, 4>(Q, K, out, BH, (int)N, scale, stream);
+        return launch_rounds<128, 4, 2>(Q, K, out, BH, (int)N, scale, stream);
+    }
     return launch_rounds<256, 4, 2>(Q, K, out, BH, (int)N, scale, stream);
 }
 
