@@ -28,8 +28,13 @@
  *     null pointers, size overflow, supported sizes, 16-byte alignment of each
  *     base pointer, overlap of output with inputs.
  *   - Inputs must be finite.  A NaN poisons its own row only.
- *   - The library keeps no mutable global state; calls from several host
- *     threads on different streams are safe.
+ *   - The library keeps no mutable global state apart from a per-device cache
+ *     of the compute-unit count; calls from several host threads on different
+ *     streams are safe.
+ *   - Environment: ATTNW_FUSED_KERNEL=twopass makes attnw_fused use its general
+ *     two-pass kernel also for the bf16 shapes that otherwise take the
+ *     round-based kernel (N a multiple of 256, d = 64 or 128); results of the
+ *     two agree to rounding of the row sum.  Read at every call.
  */
 #ifndef ATTNW_H
 #define ATTNW_H
