@@ -99,6 +99,25 @@ int attnw_gemm_scores(const void *Q, const void *K, void *S,
                       int64_t B, int64_t H, int64_t N, int64_t d,
                       float scale, int dtype, void *stream);
 
+/*
+ * Attention output with the weights kept on chip (the product the paper's
+ * Conclusion names as the next thing to fuse: Attention(Q, K, V) =
+ * softmax(Q K^T / sqrt(d_k)) V, Multi-Head Self-Attention section):
+ *
+ *   O[b][h][i][t] = sum_j P[b][h][i][j] * V[b][h][j][t],   P as in attnw_fused.
+ *
+ * Q, K, V : [B][H][N][d], read only.      O : [B][H][N][d], written, never read.
+ * P is never written to device memory: one sweep over the keys with a running
+ * row maximum and sum (Eq. 1 applied incrementally); the weights are rounded to
+ * bf16 before they multiply V on the matrix cores, the output once more at the store.
+ * Supported so far: dtype ATTNW_BF16, d = 64 or 128, N a multiple of 256
+ * (anything else: ATTNW_ERR_UNSUPPORTED).  O must not overlap Q, K or V.
+ * Validation order as for attnw_fused.
+ */
+int attnw_attention(const void *Q, const void *K, const void *V, void *O,
+                    int64_t B, int64_t H, int64_t N, int64_t d,
+                    float scale, int dtype, void *stream);
+
 /* Human-readable name of a status code; never NULL. */
 const char *attnw_status_string(int status);
 

@@ -44,6 +44,7 @@ def _load():
         lib.oracle_scores.argtypes = [vp, vp, ci, i64, i64, cf, i64, i64, vp, ci]
         lib.oracle_attention_weights.argtypes = [vp, vp, ci, i64, i64, cf, i64, i64, vp, ci]
         lib.oracle_softmax.argtypes = [vp, ci, i64, i64, i64, i64, vp, ci]
+        lib.oracle_attention_output.argtypes = [vp, vp, vp, ci, i64, i64, i64, cf, i64, i64, vp, vp, ci]
         lib.oracle_softmax_plain.argtypes = [vp, ci, i64, i64, vp]
         lib.oracle_threads_used.restype = ci
         _lib = lib
@@ -99,6 +100,24 @@ def attention_weights_bh(Q: np.ndarray, K: np.ndarray, dtype: str, scale, thread
         for h in range(H):
             out[b, h] = attention_weights(Q[b, h], K[b, h], dtype, scale, threads=threads)
     return out
+
+
+def attention_output(Q: np.ndarray, K: np.ndarray, V: np.ndarray, dtype: str, scale, rows: Optional[tuple] = None,
+                     threads: int = 0, return_weights: bool = False):
+    """Attention output of ONE head: Q, K are [N, d], V is [N, dv]; returns fp64 [r1-r0, dv]
+    (and the fp64 weights [r1-r0, N] it was formed from, on request)."""
+    Q, K, V = _as(Q, dtype), _as(K, dtype), _as(V, dtype)
+    N, d = Q.shape
+    assert K.shape == (N, d) and V.shape[0] == N
+    dv = V.shape[1]
+    r0, r1 = (0, N) if rows is None else rows
+    out = np.empty((r1 - r0, dv), dtype=np.float64)
+    P = np.empty((r1 - r0, N), dtype=np.float64)
+    rc = _load().oracle_attention_output(Q.ctypes.data, K.ctypes.data, V.ctypes.data, _DT[dtype], N, d, dv,
+                                         float(np.float32(scale)), r0, r1, out.ctypes.data, P.ctypes.data, threads)
+    if rc:
+        raise ValueError("oracle_attention_output: bad arguments")
+    return (out, P) if return_weights else out
 
 
 def softmax(S: np.ndarray, dtype: str, rows: Optional[tuple] = None, threads: int = 0) -> np.ndarray:

@@ -13,7 +13,10 @@
  *   - row softmax  sigma(Z)_ij = e^{Z_ij} / sum_k e^{Z_ik}   (Softmax section,
  *     unnumbered definition; m x n input, one distribution per row);
  *   - the max-subtracted form with m_i = max_j Z_ij   (Softmax section, Eq. 1),
- *     which has the same value and keeps exp() away from overflow.
+ *     which has the same value and keeps exp() away from overflow;
+ *   - the attention output  Attention(Q,K,V) = softmax(Q K^T / sqrt(d_k)) V
+ *     (Multi-Head Self-Attention section; the paper's Conclusion names fusing
+ *     this product into the kernel as the next step).
  *
  * Readings taken where the paper is silent (all listed in the design notes):
  * the scale is the fp32 number the caller hands to the library, widened
@@ -24,7 +27,10 @@
  * Parity pins (tests/test_oracle_pins.py): closed forms for N <= 4, row sums,
  * uniform output for Q = 0, shift invariance (Eq. 1), key/query permutation,
  * agreement of the plain definition with the max-subtracted form, and a
- * cross-check against scipy/numpy on small cases.  Nothing here is unpinned.
+ * cross-check against scipy/numpy on small cases; for the attention output:
+ * one-hot V (output = columns of P), constant V, Q = 0 (column means of V),
+ * linearity in V, joint permutation of keys and values, the N = 2 closed form.
+ * Nothing here is unpinned.
  *
  * No blocking, fusion or reordering: every function is the definition, row by
  * row.  OpenMP only splits independent rows across host threads.
@@ -170,6 +176,33 @@ int oracle_softmax_plain(const void *S, int dtype, int64_t rows, int64_t cols, d
         }
         for (int64_t j = 0; j < cols; ++j)
             out[j] = out[j] / l;
+    }
+    return 0;
+}
+
+/*
+ * Attention output of one head, rows [row_begin, row_end):
+ *   O_out[i - row_begin][t] = sum_j P[i][j] * V[j][t],  P = softmax_j(scale * Q K^T)  as above.
+ * Q, K: [N][d], V: [N][dv] row-major in `dtype`.  O_out: [(row_end-row_begin)][dv] fp64.
+ * scratch: [(row_end-row_begin)][N] fp64, receives P (the caller may want it for error bounds).
+ */
+int oracle_attention_output(const void *Q, const void *K, const void *V, int dtype, int64_t N, int64_t d, int64_t dv,
+                            float scale, int64_t row_begin, int64_t row_end, double *O_out, double *scratch,
+                            int threads)
+{
+    if (!V || !O_out || !scratch || dv < 1) return -1;
+    int rc = oracle_attention_weights(Q, K, dtype, N, d, scale, row_begin, row_end, scratch, threads);
+    if (rc) return rc;
+    const int nt = pick_threads(threads);
+#pragma omp parallel for schedule(static) num_threads(nt)
+    for (int64_t r = 0; r < row_end - row_begin; ++r) {
+        const double *p = scratch + r * N;
+        for (int64_t t = 0; t < dv; ++t) {
+            double acc = 0.0;
+            for (int64_t j = 0; j < N; ++j)
+                acc += p[j] * load_elem(V, dtype, j * dv + t);
+            O_out[r * dv + t] = acc;
+        }
     }
     return 0;
 }

@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     ATTNW_BF16,
     ATTNW_F32,
     AttnwError,
+    attnw_attention,
     attnw_fused,
     attnw_gemm_scores,
     attnw_softmax,

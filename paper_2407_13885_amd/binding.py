@@ -22,7 +22,8 @@ _ROOT = os.path.dirname(_PKG)
 _CSRC = os.path.join(_PKG, "csrc")
 _LIB = os.path.join(_PKG, "libattnw.so")
 
-EXPORTS = ("attnw_fused", "attnw_softmax", "attnw_gemm_scores", "attnw_status_string", "attnw_version")
+EXPORTS = ("attnw_fused", "attnw_softmax", "attnw_gemm_scores", "attnw_attention", "attnw_status_string",
+           "attnw_version")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -74,6 +75,8 @@ def load_library():
         lib.attnw_fused.restype = ci
         lib.attnw_gemm_scores.argtypes = [vp, vp, vp, i64, i64, i64, i64, cf, ci, vp]
         lib.attnw_gemm_scores.restype = ci
+        lib.attnw_attention.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, cf, ci, vp]
+        lib.attnw_attention.restype = ci
         lib.attnw_softmax.argtypes = [vp, vp, i64, i64, ci, vp]
         lib.attnw_softmax.restype = ci
         lib.attnw_status_string.argtypes = [ci]
@@ -128,3 +131,9 @@ def attnw_gemm_scores(Q, K, S, B: int, H: int, N: int, d: int, scale: float, dty
     """S = scale * Q K^T written to device memory; see ``attnw_gemm_scores`` in include/attnw.h."""
     _check(load_library().attnw_gemm_scores(_ptr(Q), _ptr(K), _ptr(S), B, H, N, d, float(scale), int(dtype),
                                             _stream(stream)))
+
+
+def attnw_attention(Q, K, V, O, B: int, H: int, N: int, d: int, scale: float, dtype: int, stream=None) -> None:
+    """O = softmax(scale * Q K^T) V, weights kept on chip; see ``attnw_attention`` in include/attnw.h."""
+    _check(load_library().attnw_attention(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), B, H, N, d, float(scale), int(dtype),
+                                          _stream(stream)))

@@ -1,0 +1,321 @@
+// Attention output  O = softmax(scale * Q K^T) V  with the attention weights kept on chip.
+//
+// The paper's Conclusion names the product with V as the next thing to fuse into its kernel
+// (Multi-Head Self-Attention section: Attention(Q, K, V) = softmax(Q K^T / sqrt(d_k)) V).  Once the
+// weights are not written, nothing forces two sweeps over the keys: the max-subtracted softmax
+// (Softmax section, Eq. 1) is applied incrementally -- a running row maximum m and sum l, and an
+// output accumulator that is rescaled by 2^(c m_old - c m_new) whenever the maximum grows -- and
+// one sweep over the K and V tiles suffices.
+//
+// Work split: one workgroup of 8 waves per (head, strip of 8 * QW queries); every wave owns
+// QW = 32 * QB queries and walks ALL keys, so no statistics cross waves.  Per 128-key tile:
+//   K tile  [128 keys][d]      global -> LDS directly, chunk-swizzled as in the weight kernels;
+//   V tile  transposed on the way into LDS as Vt[d][128 keys]: the second contraction runs over
+//           keys, and a matrix-core operand wants its 8 contraction elements contiguous per lane.
+// Per 32-key sub-tile and query block (all on v_mfma_f32_32x32x16_bf16, fp32 accumulate):
+//   S^T = K_sub * Q^T          lane (query l32, half h) holds keys 8i + 4h + j of its query;
+//   running max (shared by lanes l, l+32: both feed the same second contraction), p = 2^(c s - c m),
+//   l += sum p (fp32), p rounded to bf16;
+//   O^T += Vt_sub * P^T        lane (query l32, half h) holds O[query][8i + 4h + j] per 32-wide block.
+// The k-index of the second contraction is a permutation of the keys chosen so that a lane's own
+// 8 weights ARE its operand: slot 8h + e  <->  key 16m + 8 (e / 4) + 4h + e % 4.  Vt stores the keys
+// of every 16-group in that order (bits 2 and 3 of the key index swapped).
+#include "launchers.h"
+#include "qk_common.h"
+
+namespace attnw {
+namespace {
+
+__device__ __forceinline__ void dma16_untracked_a(const char* src, uint32_t lds_base)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(src) : "memory");
+#endif
+}
+
+// value of the other half-wave's lane (l ^ 32) combined with the own one
+__device__ __forceinline__ float half_max(float x)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+#else
+    return x;
+#endif
+}
+__device__ __forceinline__ float half_sum(float x)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+#else
+    return x;
+#endif
+}
+
+template <int DB, int QB>
+struct AttnCfg {
+    static constexpr int D = DB / 2;              // head dimension
+    static constexpr int NW = 8;
+    static constexpr int QW = 32 * QB;            // queries per wave
+    static constexpr int BM = QW * NW;            // queries per workgroup
+    static constexpr int BN = 128;                // keys per tile
+    static constexpr int G = DB / 32;             // 32-byte contraction groups per K row
+    static constexpr int CPR = DB / 16;           // 16-byte chunks per K / V row
+    static constexpr int DVB = D / 32;            // 32-wide blocks of the output row
+    static constexpr int K_TILE_BYTES = BN * DB;
+    static constexpr int K_LOADS = BN * CPR / 64 / NW;
+    static constexpr int V_LOADS = 2 * CPR / NW;  // wave-wide loads of 64 keys x one chunk, per wave and tile
+    static constexpr int VT_PITCH = BN * 2 + 16;  // bytes of one Vt row (one output column, 128 keys)
+    static constexpr int VT_BYTES = D * VT_PITCH;
+    static constexpr int RPL = CPR >= 16 ? 1 : 16 / CPR;
+    static constexpr int SWZ_MASK = (CPR >= 16 ? 16 : CPR) - 1;
+    static constexpr int LDS_TOTAL = 2 * K_TILE_BYTES + 2 * VT_BYTES;
+};
+
+template <int DB, int QB>
+__global__ __launch_bounds__(512)
+void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
+                      uint16_t* __restrict__ O, int N, float c, uint32_t sign_flip, uint32_t strips, uint32_t total)
+{
+    using C = AttnCfg<DB, QB>;
+    constexpr int NW = C::NW, QW = C::QW, BM = C::BM, BN = C::BN, G = C::G, CPR = C::CPR, DVB = C::DVB;
+    constexpr int K_TILE_BYTES = C::K_TILE_BYTES, K_LOADS = C::K_LOADS, V_LOADS = C::V_LOADS;
+    constexpr int VT_PITCH = C::VT_PITCH, VT_BYTES = C::VT_BYTES;
+    static_assert(2 * K_TILE_BYTES <= 65536, "the K buffers sit in the first 64 KiB of LDS (transfer base register)");
+    static_assert((2 * CPR) % NW == 0, "V tile load shape");
+
+    __shared__ __align__(1024) char lds[C::LDS_TOTAL];
+    char* const k_lds = lds;
+    char* const vt_lds = lds + 2 * K_TILE_BYTES;
+
+    const uint32_t logical = xcd_contiguous_block_id(blockIdx.x, gridDim.x);
+    if (logical >= total) return;
+    const uint32_t bh = logical / strips;
+    const uint32_t strip = logical - bh * strips;
+
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63;
+    const int l32 = lane & 31;
+    const int half = lane >> 5;
+
+    const char* Qh = reinterpret_cast<const char*>(Q) + (int64_t)bh * N * DB;
+    const char* Kh = reinterpret_cast<const char*>(K) + (int64_t)bh * N * DB;
+    const char* Vh = reinterpret_cast<const char*>(V) + (int64_t)bh * N * DB;
+    char* Oh = reinterpret_cast<char*>(O) + (int64_t)bh * N * DB;
+    const int q0 = strip * BM + wave * QW;
+
+    // ---- Q fragments (a negative scale negates Q) ----------------------------------------------------
+    u32x4 qf[QB][G];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+            qf[qb][g] = *reinterpret_cast<const u32x4*>(Qh + (int64_t)(q0 + qb * 32 + l32) * DB + (2 * g + half) * 16) ^ sign_flip;
+
+    // ---- per-lane constants ----------------------------------------------------------------------------
+    int goff[K_LOADS];
+#pragma unroll
+    for (int j = 0; j < K_LOADS; ++j) {
+        const int s = (wave + NW * j) * 64 + lane;
+        const int key = s / CPR;
+        const int ch = (s % CPR) ^ ((key / C::RPL) & C::SWZ_MASK);
+        goff[j] = key * DB + ch * 16;
+    }
+    const uint32_t k_lds_base = (uint32_t)(uintptr_t)(lds_ptr)(k_lds);
+    int kfrag_off[G];
+    {
+        const int swz = (l32 / C::RPL) & C::SWZ_MASK;
+#pragma unroll
+        for (int g = 0; g < G; ++g) kfrag_off[g] = l32 * DB + (((2 * g + half) ^ swz) * 16);
+    }
+    // V tile: wave-wide load j covers 64 consecutive keys x one 16-byte chunk (8 output columns); the
+    // 8 values go to 8 Vt rows at the key's permuted position (64 lanes -> 128 contiguous bytes per row)
+    int v_goff[V_LOADS], v_ldsoff[V_LOADS];
+#pragma unroll
+    for (int j = 0; j < V_LOADS; ++j) {
+        const int idx = wave + NW * j;
+        const int key = (idx & 1) * 64 + lane;
+        const int ch = idx >> 1;
+        const int pos = (key & ~12) | ((key & 4) << 1) | ((key & 8) >> 1);   // bits 2 and 3 swapped
+        v_goff[j] = key * DB + ch * 16;
+        v_ldsoff[j] = ch * 8 * VT_PITCH + pos * 2;
+    }
+    // Vt fragment of (block dvb, sub-tile u, group m): row dvb*32 + l32, keys u*32 + 16m + 8*half ..
+    const int vfrag_off = l32 * VT_PITCH + half * 16;
+
+    const int n_tiles = N / BN;
+    auto k_issue = [&](int tile, int buf) __attribute__((always_inline)) {
+        const char* tile_base = Kh + (int64_t)tile * (BN * DB);
+#pragma unroll
+        for (int i = 0; i < K_LOADS; ++i)
+            dma16_untracked_a(tile_base + goff[i], k_lds_base + buf * K_TILE_BYTES + (wave + NW * i) * 1024);
+    };
+    u32x4 vreg[V_LOADS];
+    auto v_load = [&](int tile) __attribute__((always_inline)) {
+        const char* tile_base = Vh + (int64_t)tile * (BN * DB);
+#pragma unroll
+        for (int j = 0; j < V_LOADS; ++j) vreg[j] = *reinterpret_cast<const u32x4*>(tile_base + v_goff[j]);
+    };
+    auto v_scatter = [&](int buf) __attribute__((always_inline)) {
+        char* base = vt_lds + buf * VT_BYTES;
+#pragma unroll
+        for (int j = 0; j < V_LOADS; ++j)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t w = vreg[j][e / 2];
+                *reinterpret_cast<uint16_t*>(base + v_ldsoff[j] + e * VT_PITCH) = (uint16_t)((e & 1) ? (w >> 16) : (w & 0xffffu));
+            }
+    };
+
+    f32x16 oacc[QB][DVB];
+    float mb_run[QB], m_run[QB], l_run[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        mb_run[qb] = kNegBig; m_run[qb] = kNegBig; l_run[qb] = 0.0f;
+#pragma unroll
+        for (int b = 0; b < DVB; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[qb][b][r] = 0.0f;
+    }
+
+    // one 128-key tile out of buffers `buf`
+    auto compute_tile = [&](auto bufc) __attribute__((always_inline)) {
+        constexpr int BUF = decltype(bufc)::value;
+        const char* kb = k_lds + BUF * K_TILE_BYTES;
+        const char* vb = vt_lds + BUF * VT_BYTES + vfrag_off;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            u32x4 kf[G];
+#pragma unroll
+            for (int g = 0; g < G; ++g) kf[g] = *reinterpret_cast<const u32x4*>(kb + u * 32 * DB + kfrag_off[g]);
+            f32x16 s[QB];
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[qb][r] = 0.0f;
+#pragma unroll
+                for (int g = 0; g < G; ++g) Mma<uint16_t>::run(s[qb], kf[g], qf[qb][g]);
+            }
+            u32x4 vf[DVB][2];
+#pragma unroll
+            for (int b = 0; b < DVB; ++b)
+#pragma unroll
+                for (int m = 0; m < 2; ++m)
+                    vf[b][m] = *reinterpret_cast<const u32x4*>(vb + b * 32 * VT_PITCH + (u * 32 + 16 * m) * 2);
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+                // running maximum, shared by the two lanes of a query
+                float tm = max3(s[qb][0], s[qb][1], s[qb][2]);
+#pragma unroll
+                for (int r = 3; r < 15; r += 2) tm = max3(tm, s[qb][r], s[qb][r + 1]);
+                const float mn = half_max(max3(tm, s[qb][15], m_run[qb]));
+                m_run[qb] = mn;
+                const float mbn = mn * c;
+                // Rescale only when some query of the wave saw its maximum grow (rare after the first tiles).
+                // Lanes whose maximum stands get the factor 2^0 = 1 exactly.
+                if (__builtin_amdgcn_ballot_w64(mbn > mb_run[qb]) != 0) {
+                    const float alpha = fast_exp2(mb_run[qb] - mbn);
+                    l_run[qb] *= alpha;
+#pragma unroll
+                    for (int b = 0; b < DVB; ++b)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) oacc[qb][b][r] *= alpha;
+                    mb_run[qb] = mbn;
+                }
+                const float mb = mb_run[qb];
+                float p[16];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) p[r] = fast_exp2(__builtin_fmaf(s[qb][r], c, -mb));
+                float sum = p[0];
+#pragma unroll
+                for (int r = 1; r < 16; ++r) sum += p[r];
+                l_run[qb] += sum;
+                // a lane's weights of group m are accumulators 8m .. 8m+7: exactly its operand of the second contraction
+#pragma unroll
+                for (int m = 0; m < 2; ++m) {
+                    u32x4 pw;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) pw[i] = pack_bf16x2(p[8 * m + 2 * i], p[8 * m + 2 * i + 1]);
+#pragma unroll
+                    for (int b = 0; b < DVB; ++b) Mma<uint16_t>::run(oacc[qb][b], vf[b][m], pw);
+                }
+            }
+        }
+    };
+
+    // ---- prologue: tile 0 --------------------------------------------------------------------------------
+    k_issue(0, 0);
+    v_load(0);
+    v_scatter(0);
+    wait_vmem();
+    __syncthreads();
+
+    // ---- the sweep: while tile t is computed, K tile t+1 lands in the other buffer and V tile t+1 waits in registers
+    auto iteration = [&](int t, auto bufc) __attribute__((always_inline)) {
+        constexpr int BUF = decltype(bufc)::value;
+        const int nxt = t + 1 < n_tiles ? t + 1 : 0;      // past the end: a valid tile, unused
+        k_issue(nxt, BUF ^ 1);
+        v_load(nxt);
+        compute_tile(bufc);
+        v_scatter(BUF ^ 1);
+        wait_vmem();
+        __syncthreads();
+    };
+    for (int t = 0; t < n_tiles; t += 2) {
+        iteration(t, IC<0>{});
+        iteration(t + 1, IC<1>{});
+    }
+
+    // ---- normalise, round once, store: a lane owns runs of 4 consecutive output columns of its query -----------
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        const float inv = 1.0f / half_sum(l_run[qb]);
+        char* orow = Oh + (int64_t)(q0 + qb * 32 + l32) * DB + half * 8;
+#pragma unroll
+        for (int b = 0; b < DVB; ++b)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                u32x2 w = {pack_bf16x2(oacc[qb][b][4 * i] * inv, oacc[qb][b][4 * i + 1] * inv),
+                           pack_bf16x2(oacc[qb][b][4 * i + 2] * inv, oacc[qb][b][4 * i + 3] * inv)};
+                *reinterpret_cast<u32x2*>(orow + (b * 32 + 8 * i) * 2) = w;
+            }
+    }
+}
+
+template <int DB, int QB>
+hipError_t launch_attention_t(const void* Q, const void* K, const void* V, void* O, int64_t BH, int N, float scale,
+                              hipStream_t stream)
+{
+    using C = AttnCfg<DB, QB>;
+    const uint32_t strips = (uint32_t)(N / C::BM);
+    const uint64_t total = (uint64_t)BH * strips;
+    const uint32_t grid = (uint32_t)((total + 7) / 8 * 8);
+    const float c = fabsf(scale) * kLog2e;
+    const uint32_t flip = scale < 0.0f ? Mma<uint16_t>::kSignMask : 0u;
+    hipLaunchKernelGGL((attention_kernel<DB, QB>), dim3(grid), dim3(512), 0, stream, static_cast<const uint16_t*>(Q),
+                       static_cast<const uint16_t*>(K), static_cast<const uint16_t*>(V), static_cast<uint16_t*>(O), N, c,
+                       flip, strips, (uint32_t)total);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+bool attention_supported(int64_t BH, int64_t N, int64_t d)
+{
+    if (d != 64 && d != 128) return false;
+    if (N < 256 || (N % 256) != 0 || N > ((int64_t)1 << 24)) return false;
+    return BH * (N / 256) <= (int64_t)0x7ffffff0;
+}
+
+hipError_t launch_attention(const void* Q, const void* K, const void* V, void* O, int64_t BH, int64_t N, int64_t d,
+                            float scale, hipStream_t stream)
+{
+    if (d == 128) return launch_attention_t<256, 1>(Q, K, V, O, BH, (int)N, scale, stream);
+    // two query blocks per wave (512-query strips) when that still gives every compute unit a workgroup
+    if ((N % 512) == 0 && BH * (N / 512) >= 200) return launch_attention_t<128, 2>(Q, K, V, O, BH, (int)N, scale, stream);
+    return launch_attention_t<128, 1>(Q, K, V, O, BH, (int)N, scale, stream);
+}
+
+}  // namespace attnw

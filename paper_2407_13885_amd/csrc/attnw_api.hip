@@ -72,6 +72,25 @@ int attnw_gemm_scores(const void* Q, const void* K, void* S, int64_t B, int64_t 
     return run_qk(true, Q, K, S, B, H, N, d, scale, dtype, stream);
 }
 
+int attnw_attention(const void* Q, const void* K, const void* V, void* O, int64_t B, int64_t H, int64_t N, int64_t d,
+                    float scale, int dtype, void* stream)
+{
+    if (dtype != ATTNW_F32 && dtype != ATTNW_BF16) return ATTNW_ERR_DTYPE;
+    if (B < 0 || H < 0 || N < 0 || d < 0) return ATTNW_ERR_SHAPE;
+    if (B == 0 || H == 0 || N == 0) return ATTNW_OK;          // empty problem
+    if (!Q || !K || !V || !O) return ATTNW_ERR_NULL;
+    int64_t BH, elems, bytes;
+    if (mul_overflows(B, H, &BH) || mul_overflows(BH, N, &elems) || mul_overflows(elems, d, &elems) ||
+        mul_overflows(elems, elem_size(dtype), &bytes))
+        return ATTNW_ERR_SHAPE;
+    if (dtype != ATTNW_BF16 || !attnw::attention_supported(BH, N, d)) return ATTNW_ERR_UNSUPPORTED;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O)) return ATTNW_ERR_ALIGN;
+    if (overlaps(O, bytes, Q, bytes) || overlaps(O, bytes, K, bytes) || overlaps(O, bytes, V, bytes))
+        return ATTNW_ERR_ALIAS;
+    const hipError_t e = attnw::launch_attention(Q, K, V, O, BH, N, d, scale, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? ATTNW_OK : ATTNW_ERR_LAUNCH;
+}
+
 int attnw_softmax(const void* S, void* P, int64_t rows, int64_t cols, int dtype, void* stream)
 {
     if (dtype != ATTNW_F32 && dtype != ATTNW_BF16) return ATTNW_ERR_DTYPE;

@@ -36,7 +36,7 @@ _M2 = np.uint64(0x94D049BB133111EB)
 _STREAM_MUL = np.uint64(0xD1B54A32D192ED03)
 _CHUNK = 1 << 22
 
-STREAM_Q, STREAM_K, STREAM_S, STREAM_MASK, STREAM_QROW, STREAM_KROW = range(6)
+STREAM_Q, STREAM_K, STREAM_S, STREAM_MASK, STREAM_QROW, STREAM_KROW, STREAM_V = range(7)
 
 
 def _mix(x: np.ndarray) -> np.ndarray:
@@ -192,6 +192,13 @@ def fused_inputs(name: str, dtype: str, B: int, H: int, N: int, d: int, seed: in
     if scale is None:
         scale = 1.0 / np.sqrt(np.float64(d))
     return FusedInputs(name, dtype, B, H, N, d, np.float32(scale), store(q, dtype), store(k, dtype))
+
+
+def value_inputs(x: FusedInputs, seed: int) -> np.ndarray:
+    """V ~ N(0,1) i.i.d., [B, H, N, d] in the storage type of ``x`` (stream of its own: Q and K of the
+    same seed are unchanged)."""
+    n = x.B * x.H * x.N * x.d
+    return store(standard_normal(seed, STREAM_V, n).reshape(x.B, x.H, x.N, x.d), x.dtype)
 
 
 def softmax_inputs(name: str, dtype: str, rows: int, cols: int, seed: int, sigma: float = 1.0,

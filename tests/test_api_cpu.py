@@ -91,6 +91,22 @@ def test_gemm_scores_shares_the_rules(lib):
     assert g(QA, KA, QA, 1, 1, 128, 64, 0.125, F32, None) == E_ALIAS
 
 
+def test_attention_validation(lib):
+    a = lib.attnw_attention
+    VA, OA = 0x30000000, 0x50000000
+    assert a(QA, KA, VA, OA, 1, 1, 256, 64, 0.125, 9, None) == E_DTYPE
+    assert a(QA, KA, VA, OA, 1, -1, 256, 64, 0.125, BF16, None) == E_SHAPE
+    assert a(None, None, None, None, 0, 1, 256, 64, 0.125, BF16, None) == OK
+    assert a(QA, KA, None, OA, 1, 1, 256, 64, 0.125, BF16, None) == E_NULL
+    assert a(QA, KA, VA, None, 1, 1, 256, 64, 0.125, BF16, None) == E_NULL
+    assert a(QA, KA, VA, OA, 1, 1, 256, 64, 0.125, F32, None) == E_UNSUP        # bf16 only so far
+    assert a(QA, KA, VA, OA, 1, 1, 320, 64, 0.125, BF16, None) == E_UNSUP       # N a multiple of 256
+    assert a(QA, KA, VA, OA, 1, 1, 256, 32, 0.125, BF16, None) == E_UNSUP       # d = 64 or 128
+    assert a(QA, KA, VA + 2, OA, 1, 1, 256, 64, 0.125, BF16, None) == E_ALIGN
+    assert a(QA, KA, VA, VA, 1, 1, 256, 64, 0.125, BF16, None) == E_ALIAS
+    assert a(QA, KA, VA, QA + 256 * 64 * 2 - 16, 1, 1, 256, 64, 0.125, BF16, None) == E_ALIAS
+
+
 def test_softmax_validation(lib):
     s = lib.attnw_softmax
     assert s(QA, PA, 4, 4, -1, None) == E_DTYPE

@@ -1,0 +1,102 @@
+"""GPU parity of attnw_attention (O = softmax(scale Q K^T) V with the weights kept on chip) against the
+fp64 oracle.
+
+Tolerance, from the arithmetic of the kernel: the weights are rounded to bf16 (8-bit significand:
+relative 2^-8 each at worst) before they multiply V, everything else up to the store is fp32, and
+the result is rounded to bf16 once more (2^-8 |O|).  Hence
+|O - O_ref| <= 2^-8 (sum_j P_ij |V_jt| + |O_ref|)  up to fp32 effects, for which 2 % of that bound
+plus 1e-6 of the first sum is allowed on top.  (Rows with one dominant key come close to the bound;
+flat rows stay far below it because the rounding errors of many weights average out.)"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2407_13885_amd as attnw
+from paper_2407_13885_amd import workloads as wl
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _gpu():
+    gu.require_gpu()
+
+
+def _run(x, V, guard=4096):
+    Q, K, Vd = gu.to_dev(x.Q, "bf16"), gu.to_dev(x.K, "bf16"), gu.to_dev(V, "bf16")
+    O, canary = gu.empty_like_out((x.B, x.H, x.N, x.d), "bf16", guard)
+    attnw.attnw_attention(Q, K, Vd, O, x.B, x.H, x.N, x.d, float(x.scale), attnw.ATTNW_BF16)
+    torch.cuda.synchronize()
+    assert gu.guards_intact(canary), "attention kernel wrote outside O"
+    return O
+
+
+def _check_rows(got, x, V, b, h, rows, what):
+    """rows: (r0, r1) range or list of single rows."""
+    Vw = np.abs(wl.widen(V[b, h], "bf16"))
+    spans = [rows] if isinstance(rows, tuple) else [(r, r + 1) for r in rows]
+    for r0, r1 in spans:
+        ref, P = oracle.attention_output(x.Q[b, h], x.K[b, h], V[b, h], "bf16", x.scale, rows=(r0, r1), return_weights=True)
+        A = P @ Vw
+        tol = 2.0 ** -8 * (A + np.abs(ref)) * 1.02 + 1e-6 * A
+        err = np.abs(got[r0:r1] - ref)
+        assert np.isfinite(got[r0:r1]).all(), f"{what}: non-finite output"
+        if (err > tol).any():
+            i = np.unravel_index(np.argmax(err / tol), err.shape)
+            raise AssertionError(f"{what} rows {r0}..{r1}: {int((err > tol).sum())} elements beyond the bound; worst at {i}: "
+                                 f"got {got[r0:r1][i]:.6e} ref {ref[i]:.6e} err {err[i]:.3e} tol {tol[i]:.3e}")
+
+
+@pytest.mark.parametrize("B,H,N,d", [(1, 2, 256, 64), (1, 3, 512, 64), (2, 2, 512, 128), (1, 1, 1024, 128),
+                                     (1, 100, 1024, 64)])
+def test_attention_bf16_small(B, H, N, d):
+    x = wl.fused_inputs("t", "bf16", B, H, N, d, seed=800 + H + N + d)
+    V = wl.value_inputs(x, seed=801 + N)
+    O = gu.to_f64(_run(x, V))
+    for b in range(B):
+        for h in range(H if H <= 4 else 3):          # every head of the small cases, three of the many-head case
+            hh = h if H <= 4 else (0, H // 2, H - 1)[h]
+            _check_rows(O[b, hh], x, V, b, hh, (0, N), f"attention {B}x{H}x{N}x{d} head ({b},{hh})")
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_attention_negative_scale_sharp_rows_and_special_values(d):
+    x = wl.fused_inputs("t", "bf16", 1, 2, 768, d, seed=41 + d, scale=-1.0 / math.sqrt(d), row_factor=(0.5, 3.0))
+    V = wl.value_inputs(x, seed=42 + d)
+    O = gu.to_f64(_run(x, V))
+    for h in range(2):
+        _check_rows(O[0, h], x, V, 0, h, (0, 768), f"negative scale d={d} head {h}")
+    # Q = 0: uniform weights, the output is the column mean of V for every query
+    x.Q[...] = 0
+    O0 = gu.to_f64(_run(x, V))
+    mean = wl.widen(V[0, 0], "bf16").mean(axis=0)
+    assert np.abs(O0[0, 0] - mean).max() <= 2.0 ** -8 * np.abs(wl.widen(V[0, 0], "bf16")).mean(axis=0).max()
+    # constant V rows: every output row equals that row exactly (weights sum to 1, up to their rounding)
+    Vc = np.broadcast_to(V[:, :, :1, :], V.shape).copy()
+    Oc = gu.to_f64(_run(x, Vc))
+    v = wl.widen(Vc[0, 1, 0], "bf16")
+    assert np.abs(Oc[0, 1] - v).max() <= 2.0 ** -7 * np.abs(v).max()
+
+
+@pytest.mark.parametrize("name", ["c4", "c5"])
+def test_attention_full_size_sampled_rows(name):
+    x = wl.CONFIGS[name]()
+    V = wl.value_inputs(x, seed=77)
+    O = gu.to_f64(_run(x, V))
+    assert np.isfinite(O).all()
+    rng = np.random.default_rng(9)
+    for h in range(x.H):
+        rows = sorted({0, 31, 32, 255, 256, x.N // 2, x.N - 257, x.N - 1} | set(rng.integers(0, x.N, size=8).tolist()))
+        _check_rows(O[0, h], x, V, 0, h, rows, f"{name} attention head {h}")
+
+
+def test_attention_is_deterministic():
+    x = wl.fused_inputs("t", "bf16", 1, 2, 512, 64, seed=6)
+    V = wl.value_inputs(x, seed=7)
+    a, b = _run(x, V, guard=0 + 64), _run(x, V, guard=0 + 64)
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))

@@ -228,3 +228,65 @@ def test_bad_arguments_are_rejected():
         oracle.softmax(np.zeros((2, 2)), "f64", rows=(1, 3))
     with pytest.raises(TypeError):
         oracle.softmax(np.zeros((2, 2), dtype=np.float32), "f64")
+
+
+# ---- attention output  O = softmax(scale Q K^T) V  (Multi-Head Self-Attention section) -------------
+# Pins chosen so that a transposed V, a contraction over the wrong axis, weights that are not
+# normalised, or V rows matched to the wrong keys each fail at least one of them.
+
+def test_output_with_one_hot_values_is_a_column_block_of_the_weights():
+    r = _rng(30)
+    N, d, dv = 12, 5, 7
+    Q, K = r.standard_normal((N, d)), r.standard_normal((N, d))
+    V = np.zeros((N, dv))
+    V[np.arange(dv) + 2, np.arange(dv)] = 1.0          # V[j][t] = 1 iff j = t + 2
+    O = oracle.attention_output(Q, K, V, "f64", 0.7)
+    P = oracle.attention_weights(Q, K, "f64", 0.7)
+    assert np.array_equal(O, P[:, 2:2 + dv])
+
+
+def test_output_constant_values_and_zero_queries():
+    r = _rng(31)
+    N, d, dv = 9, 4, 6
+    Q, K, V = r.standard_normal((N, d)), r.standard_normal((N, d)), r.standard_normal((N, dv))
+    v = r.standard_normal(dv)
+    O = oracle.attention_output(Q, K, np.tile(v, (N, 1)), "f64", 1.3)
+    assert np.abs(O - v).max() < TIGHT                 # rows of the weights sum to 1
+    O0 = oracle.attention_output(np.zeros((N, d)), K, V, "f64", 1.3)
+    assert np.abs(O0 - V.mean(axis=0)).max() < TIGHT   # uniform weights: column means of V
+
+
+def test_output_closed_form_two_keys():
+    # d = 1, q_i = 1, k = (a, b): weights (s(a-b), s(b-a)), s the logistic function
+    a, b = 0.25, -1.5
+    Q = np.ones((2, 1)); K = np.array([[a], [b]]); V = np.array([[2.0, -1.0, 0.5], [10.0, 3.0, -4.0]])
+    w0 = 1.0 / (1.0 + math.exp(b - a))
+    want = w0 * V[0] + (1.0 - w0) * V[1]
+    O = oracle.attention_output(Q, K, V, "f64", 1.0)
+    assert np.abs(O - want).max() < TIGHT
+
+
+def test_output_linear_in_values_and_invariant_under_joint_key_value_permutation():
+    r = _rng(32)
+    N, d, dv = 17, 8, 5
+    Q, K = r.standard_normal((N, d)), r.standard_normal((N, d))
+    V1, V2 = r.standard_normal((N, dv)), r.standard_normal((N, dv))
+    O1, O2 = oracle.attention_output(Q, K, V1, "f64", 0.4), oracle.attention_output(Q, K, V2, "f64", 0.4)
+    assert np.abs(oracle.attention_output(Q, K, 2.0 * V1 - 3.0 * V2, "f64", 0.4) - (2.0 * O1 - 3.0 * O2)).max() < 1e-13
+    perm = r.permutation(N)
+    assert np.abs(oracle.attention_output(Q, K[perm], V1[perm], "f64", 0.4) - O1).max() < 1e-13
+    # permuting the values alone must change the result (V rows are tied to keys)
+    assert np.abs(oracle.attention_output(Q, K, V1[perm], "f64", 0.4) - O1).max() > 1e-3
+
+
+@pytest.mark.parametrize("n,d,dv", [(1, 4, 3), (50, 16, 16), (130, 64, 64)])
+def test_output_against_numpy_scipy(n, d, dv):
+    r = _rng(200 + n)
+    Q, K, V = r.standard_normal((n, d)), r.standard_normal((n, d)), r.standard_normal((n, dv))
+    c = np.float32(1.0 / math.sqrt(d))
+    want = scipy.special.softmax(np.float64(c) * (Q @ K.T), axis=-1) @ V
+    got, P = oracle.attention_output(Q, K, V, "f64", c, return_weights=True)
+    assert np.abs(got - want).max() < 1e-13
+    assert np.array_equal(P, oracle.attention_weights(Q, K, "f64", c))
+    rows = oracle.attention_output(Q, K, V, "f64", c, rows=(n // 2, n))
+    assert np.array_equal(rows, got[n // 2:])
