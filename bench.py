@@ -128,7 +128,10 @@ def bench_softmax(cfg, steps, warmup):
     return rec, x
 
 
-def bench_fused(cfg, steps, warmup, with_unfused=True):
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16, published
+
+
+def bench_fused(cfg, steps, warmup, with_unfused=True, with_attention=True):
     import torch
     import paper_2407_13885_amd as attnw
     x = cfg()
@@ -184,9 +187,35 @@ def bench_fused(cfg, steps, warmup, with_unfused=True):
         }
         rec["fused_vs_unfused_speedup"] = round(ev_p / ev, 3)
         del S
+    if with_attention and x.dtype == "bf16" and x.d in (64, 128) and x.N % 256 == 0:
+        # the next step after the weights: O = P V with P kept on chip (nothing of size N^2 touches HBM)
+        import numpy as np
+        Vh = wl_value_inputs(x)
+        Vd = _dev(Vh, x.dtype)
+        O = torch.empty((x.B, x.H, x.N, x.d), dtype=tdt, device="cuda")
+
+        def call_attn(i):
+            attnw.attnw_attention(Q, K, Vd, O, x.B, x.H, x.N, x.d, scale, dt, stream)
+
+        wall_a, ev_a, k_a, w_a = _time_calls(call_attn, 1, steps, warmup)
+        flops = 4.0 * x.elements * x.d
+        tf = flops / (ev_a * 1e-3) * 1e-12
+        rec["attention_output"] = {
+            "call": "attnw_attention", "ms_per_step": round(wall_a, 5), "kernel_ms": round(ev_a, 5),
+            "steps": k_a, "warmup": w_a, "mfma_TFLOPs": round(tf, 1),
+            "roofline": {"bound": "mfma", "kernel": "attention_kernel", "achieved": round(tf, 1),
+                         "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4)},
+            "elements_per_s": x.elements / (wall_a * 1e-3),
+        }
+        del O, Vd
     del P
     torch.cuda.empty_cache()
     return rec, x
+
+
+def wl_value_inputs(x):
+    from paper_2407_13885_amd import workloads as wl
+    return wl.value_inputs(x, seed=12345)
 
 
 def cpu_baseline_fused(x, rows_per_head=1024):
@@ -250,6 +279,7 @@ def main() -> int:
     ap.add_argument("--only", action="store_true", help="measure the headline workload only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-unfused", action="store_true", help="skip the unfused pair (score GEMM, then softmax)")
+    ap.add_argument("--no-attention", action="store_true", help="skip attnw_attention (O = P V with P kept on chip)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch one plain elementwise copy of 1 GiB (read 1 GiB, write 1 GiB): the known-size "
                          "kernel that rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -287,7 +317,8 @@ def main() -> int:
             results[name], inputs[name] = bench_softmax(wl.c2, args.steps, args.warmup)
         else:
             results[name], inputs[name] = bench_fused(wl.CONFIGS[name], args.steps, args.warmup,
-                                                      with_unfused=not args.no_unfused)
+                                                      with_unfused=not args.no_unfused,
+                                                      with_attention=not args.no_attention)
         if name != args.workload:
             inputs.pop(name)
 
