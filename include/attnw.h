@@ -31,10 +31,12 @@
  *   - The library keeps no mutable global state apart from a per-device cache
  *     of the compute-unit count; calls from several host threads on different
  *     streams are safe.
- *   - Environment: ATTNW_FUSED_KERNEL=twopass makes attnw_fused use its general
- *     two-pass kernel also for the bf16 shapes that otherwise take the
- *     round-based kernel (N a multiple of 256, d = 64 or 128); results of the
- *     two agree to rounding of the row sum.  Read at every call.
+ *   - Environment: ATTNW_FUSED_KERNEL=twopass makes attnw_fused and
+ *     attnw_gemm_scores use the general two-pass kernel also for the bf16
+ *     shapes that otherwise take the round-based kernel (N a multiple of 256;
+ *     d = 64 or 128 for attnw_fused, d = 64 for attnw_gemm_scores); fused
+ *     results of the two agree to rounding of the row sum, scores bit for
+ *     bit.  Read at every call.
  */
 #ifndef ATTNW_H
 #define ATTNW_H

@@ -15,11 +15,13 @@ hipError_t launch_softmax(DType dt, const void* S, void* P, int64_t rows, int64_
 hipError_t launch_qk(DType dt, bool scores_only, const void* Q, const void* K, void* out,
                      int64_t BH, int64_t N, int64_t d, float scale, hipStream_t stream);
 
-// Fused attention weights, bf16, by the round-based kernel (statistics of one strip gathered while the
-// weights of the previous one are written).  Only for the shapes qk_rounds_supported() accepts.
+// bf16, by the round-based kernel: fused attention weights (statistics of one strip gathered while the
+// weights of the previous one are written) or, with scores_only, the scaled scores (one sweep per
+// strip through the same staging and store path; d = 64 only).  Only for the shapes
+// qk_rounds_supported() accepts.
 bool qk_rounds_supported(int64_t BH, int64_t N, int64_t d);
-hipError_t launch_qk_rounds(const void* Q, const void* K, void* out, int64_t BH, int64_t N, int64_t d, float scale,
-                            hipStream_t stream);
+hipError_t launch_qk_rounds(bool scores_only, const void* Q, const void* K, void* out, int64_t BH, int64_t N, int64_t d,
+                            float scale, hipStream_t stream);
 
 // Attention output O = softmax(scale Q K^T) V, bf16, d = 64 or 128, N a multiple of 256.
 bool attention_supported(int64_t BH, int64_t N, int64_t d);

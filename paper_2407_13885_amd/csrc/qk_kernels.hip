@@ -415,9 +415,11 @@ hipError_t launch_qk(DType dt, bool scores_only, const void* Q, const void* K, v
 {
     if (dt == DType::F32) return launch_qk_t<float>(scores_only, Q, K, out, BH, (int)N, (int)d, scale, stream);
     // ATTNW_FUSED_KERNEL=twopass keeps bf16 problems on the two-pass kernel above (tests compare the two)
-    if (!scores_only && qk_rounds_supported(BH, N, d)) {
+    // (scores with 256-byte rows stay here: two co-resident workgroups of this kernel stream them faster)
+    if (qk_rounds_supported(BH, N, d) && (!scores_only || d == 64)) {
         const char* force = getenv("ATTNW_FUSED_KERNEL");
-        if (!(force && strcmp(force, "twopass") == 0)) return launch_qk_rounds(Q, K, out, BH, N, d, scale, stream);
+        if (!(force && strcmp(force, "twopass") == 0))
+            return launch_qk_rounds(scores_only, Q, K, out, BH, N, d, scale, stream);
     }
     return launch_qk_t<uint16_t>(scores_only, Q, K, out, BH, (int)N, (int)d, scale, stream);
 }

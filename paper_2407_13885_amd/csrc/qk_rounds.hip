@@ -77,7 +77,7 @@ struct RoundsCfg {
     static constexpr int LDS_TOTAL = LDS_K + LDS_ST + LDS_STAT;
 };
 
-template <int DB, int WQ, int WK>
+template <int DB, int WQ, int WK, bool SCORES>
 __global__ __launch_bounds__(64 * WQ * WK)
 void qk_rounds_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, uint16_t* __restrict__ out,
                       int N, float c, uint32_t sign_flip, uint32_t strips_per_head, uint32_t total_strips)
@@ -185,7 +185,7 @@ void qk_rounds_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
         __syncthreads();
 #pragma unroll
         for (int b = 0; b < NBUF; ++b) k_issue(b, b);
-        load_q(qf[1], s0);
+        load_q(qf[SCORES ? 0 : 1], s0);
         wait_vmem_le<(NBUF - 1) * LOADS>();       // tile 0 (the younger Q loads only make this stricter)
         __syncthreads();
 
@@ -227,7 +227,8 @@ void qk_rounds_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
 #pragma unroll
                     for (int e = 0; e < EP; ++e) {
                         const int r = ci * EP + e;
-                        pv[r] = fast_exp2(__builtin_fmaf(cur[0][r], c, -bias));
+                        if constexpr (SCORES) pv[r] = cur[0][r] * c;
+                        else pv[r] = fast_exp2(__builtin_fmaf(cur[0][r], c, -bias));
                     }
                     constexpr int r_end = (ci + 1) * EP;
                     if constexpr (r_end % 2 == 0) {
@@ -371,14 +372,22 @@ void qk_rounds_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
             return out_h + (int64_t)(strip * BS + wq * 32) * (int64_t)N * 2;
         };
 
-        round(IC<0>{}, IC<1>{}, nullptr);                  // first strip: statistics only
-        for (uint32_t s = s0 + 1; s < s1; ++s) {
+        if constexpr (SCORES) {
+            // scaled scores: no statistics, every round writes its own strip
+            for (uint32_t s = s0; s < s1; ++s) {
+                if (s > s0) load_q(qf[0], s);
+                round(IC<1>{}, IC<0>{}, rows_of(s));
+            }
+        } else {
+            round(IC<0>{}, IC<1>{}, nullptr);                  // first strip: statistics only
+            for (uint32_t s = s0 + 1; s < s1; ++s) {
+                handover();
+                load_q(qf[1], s);
+                round(IC<1>{}, IC<1>{}, rows_of(s - 1));
+            }
             handover();
-            load_q(qf[1], s);
-            round(IC<1>{}, IC<1>{}, rows_of(s - 1));
+            round(IC<1>{}, IC<0>{}, rows_of(s1 - 1));          // last strip: weights only
         }
-        handover();
-        round(IC<1>{}, IC<0>{}, rows_of(s1 - 1));          // last strip: weights only
     }
     wait_vmem();   // no K transfer may be in flight when the workgroup's LDS is released
 }
@@ -397,7 +406,7 @@ int compute_units()
     return n;
 }
 
-template <int DB, int WQ, int WK>
+template <int DB, int WQ, int WK, bool SCORES>
 hipError_t launch_rounds(const void* Q, const void* K, void* out, int64_t BH, int N, float scale, hipStream_t stream)
 {
     using C = RoundsCfg<DB, WQ, WK>;
@@ -405,9 +414,10 @@ hipError_t launch_rounds(const void* Q, const void* K, void* out, int64_t BH, in
     const uint32_t total = (uint32_t)(BH * strips_per_head);
     uint32_t grid = (uint32_t)((compute_units() + 7) / 8 * 8);
     if (grid > total) grid = (total + 7) / 8 * 8;
-    const float c = fabsf(scale) * kLog2e;
-    const uint32_t flip = scale < 0.0f ? Mma<uint16_t>::kSignMask : 0u;
-    hipLaunchKernelGGL((qk_rounds_kernel<DB, WQ, WK>), dim3(grid), dim3(64 * WQ * WK), 0, stream,
+    // weights: exponent scale |scale| log2(e) with the sign folded into Q; scores: the scale itself
+    const float c = SCORES ? scale : fabsf(scale) * kLog2e;
+    const uint32_t flip = (!SCORES && scale < 0.0f) ? Mma<uint16_t>::kSignMask : 0u;
+    hipLaunchKernelGGL((qk_rounds_kernel<DB, WQ, WK, SCORES>), dim3(grid), dim3(64 * WQ * WK), 0, stream,
                        static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K), static_cast<uint16_t*>(out), N, c,
                        flip, strips_per_head, total);
     return hipGetLastError();
@@ -424,20 +434,25 @@ bool qk_rounds_supported(int64_t BH, int64_t N, int64_t d)
     return BH * (N / 128) <= (int64_t)0x7fffffff;
 }
 
-hipError_t launch_qk_rounds(const void* Q, const void* K, void* out, int64_t BH, int64_t N, int64_t d, float scale,
-                            hipStream_t stream)
+hipError_t launch_qk_rounds(bool scores_only, const void* Q, const void* K, void* out, int64_t BH, int64_t N, int64_t d,
+                            float scale, hipStream_t stream)
 {
+    auto go = [&](auto db, auto wq, auto wk) {
+        constexpr int DB = decltype(db)::value, WQ = decltype(wq)::value, WK = decltype(wk)::value;
+        return scores_only ? launch_rounds<DB, WQ, WK, true>(Q, K, out, BH, (int)N, scale, stream)
+                           : launch_rounds<DB, WQ, WK, false>(Q, K, out, BH, (int)N, scale, stream);
+    };
     if (d == 64) {
         // Few strips per workgroup: lists of 1 or 2 strips leave some workgroups with twice the work of
         // others and make the statistics-only and weights-only rounds a large share.  Strips of 64 queries
         // (2 x 4 waves, 256-key tiles) double the list lengths; K traffic per element doubles, which small
         // problems can afford.  (d = 128 has no LDS for 256-key tiles.)
         const int64_t strips128 = BH * (N / 128);
-        if (strips128 < 4 * (int64_t)compute_units() && (N % 512) == 0)
-            return launch_rounds<128, 2, 4>(Q, K, out, BH, (int)N, scale, stream);
-        return launch_rounds<128, 4, 2>(Q, K, out, BH, (int)N, scale, stream);
+        if (strips128 < 4 * (int64_t)compute_units() && (N % 512) == 0) return go(IC<128>{}, IC<2>{}, IC<4>{});
+        return go(IC<128>{}, IC<4>{}, IC<2>{});
     }
-    return launch_rounds<256, 4, 2>(Q, K, out, BH, (int)N, scale, stream);
+    if (scores_only) return hipErrorInvalidValue;   // the caller keeps scores with 256-byte rows on the general kernel
+    return launch_rounds<256, 4, 2, false>(Q, K, out, BH, (int)N, scale, stream);
 }
 
 }  // namespace attnw

@@ -187,3 +187,33 @@ def test_gemm_scores_and_unfused_pair(dtype, N, d):
     s_host = S.view(2 * N, N).cpu()
     s_np = s_host.numpy() if dtype == "f32" else s_host.view(torch.int16).numpy().view(np.uint16)
     gu.check_weights(gu.to_f64(P), oracle.softmax(s_np, dtype), dtype, f"unfused softmax {dtype}")
+
+
+# ---- score GEMM on the shapes the round-based kernel serves ------------------------------------
+
+def _check_scores(x, S, what):
+    got = gu.to_f64(S)
+    d = x.Q.shape[-1]
+    Qa, Ka = np.abs(wl.widen(x.Q, "bf16")), np.abs(wl.widen(x.K, "bf16"))
+    B, H = x.Q.shape[:2]
+    for b in range(B):
+        for h in range(H):
+            ref = oracle.scores(x.Q[b, h], x.K[b, h], "bf16", x.scale)
+            acc_bound = d * 2.0 ** -24 * abs(float(x.scale)) * (Qa[b, h] @ Ka[b, h].T)
+            assert (np.abs(got[b, h] - ref) <= acc_bound + 2.0 ** -8 * np.abs(ref) + 1e-30).all(), f"{what} head {b},{h}"
+
+
+@pytest.mark.parametrize("B,H,N,d", [(3, 100, 256, 64), (1, 5, 512, 128), (2, 2, 1536, 64), (1, 1, 2048, 128)])
+def test_gemm_scores_round_kernel_shapes(B, H, N, d):
+    x = wl.fused_inputs("t", "bf16", B, H, N, d, seed=800 + H + N + d)
+    _check_scores(x, gu.run_scores(x, guard=8192), f"round-kernel scores {B}x{H}x{N}x{d}")
+
+
+def test_gemm_scores_round_kernel_negative_scale_matches_general_kernel(monkeypatch):
+    x = wl.fused_inputs("t", "bf16", 1, 3, 512, 64, seed=77, scale=-0.37)
+    S = gu.run_scores(x, guard=4096)
+    _check_scores(x, S, "round-kernel scores, negative scale")
+    # the general kernel accumulates in the same order: identical bits
+    monkeypatch.setenv("ATTNW_FUSED_KERNEL", "twopass")
+    S2 = gu.run_scores(x, guard=4096)
+    assert torch.equal(S.view(torch.int16), S2.view(torch.int16))
