@@ -7,8 +7,9 @@ One "step" is one call of the library on one batch of seeded synthetic input
 already resident in HBM.  The headline workload (top-level ``value``) is the
 fused kernel on configuration c4 (B=1 H=16 N=4096 d=128 bf16, the paper's d_k
 and its largest fused n); the same JSON line carries, under ``workloads``, the
-dedicated softmax on c2, the fused kernel on c3 and c5, and the unfused pair
-(score GEMM, then softmax) on c3..c5 for the fused-vs-unfused ratio.
+dedicated softmax on c2, the fused kernel on c3 and c5, the unfused pair
+(score GEMM, then softmax) and the three-kernel pipeline (multiply, scaling,
+softmax) on c3..c5 for the fused-vs-unfused ratios, and the attention output.
 
 Timing: W untimed calls, then exactly K calls bracketed by a device
 synchronisation on both sides (wall clock -> ``ms_per_step`` and ``value``) and
@@ -175,17 +176,36 @@ def bench_fused(cfg, steps, warmup, with_unfused=True, with_attention=True):
             call_gemm(i)
             call_sm(i)
 
+        # the paper's three separate kernels: multiply (scale 1), scaling in place, softmax
+        def call_scale(i):
+            attnw.attnw_scale(S[i], S[i], x.elements, scale, dt, stream)
+
+        def call_three(i):
+            attnw.attnw_gemm_scores(Q, K, S[i], x.B, x.H, x.N, x.d, 1.0, dt, stream)
+            call_scale(i)
+            call_sm(i)
+
         wall_p, ev_p, _, _ = _time_calls(call_pair, n_sets, steps, warmup)
         _, ev_g, _, _ = _time_calls(call_gemm, n_sets, steps, warmup)
         _, ev_s, _, _ = _time_calls(call_sm, n_sets, steps, warmup)
+        wall_3, ev_3, _, _ = _time_calls(call_three, n_sets, steps, warmup)
+        _, ev_c, _, _ = _time_calls(call_scale, n_sets, steps, warmup)
         unf_bytes = x.algorithmic_bytes + 2 * out_bytes      # + write S, read S
+        unf3_bytes = unf_bytes + 2 * out_bytes               # + read S, write S in the scaling kernel
         rec["unfused"] = {
             "ms_per_step": round(wall_p, 5), "kernel_ms": round(ev_p, 5),
             "gemm_scores_ms": round(ev_g, 5), "softmax_ms": round(ev_s, 5),
             "elements_per_s": x.elements / (wall_p * 1e-3),
             "algorithmic_bytes": unf_bytes, "hbm_GBps": round(unf_bytes / (ev_p * 1e-3) * 1e-9, 1),
         }
+        rec["unfused_three_kernels"] = {
+            "ms_per_step": round(wall_3, 5), "kernel_ms": round(ev_3, 5), "scale_ms": round(ev_c, 5),
+            "scale_hbm_GBps": round(2 * out_bytes / (ev_c * 1e-3) * 1e-9, 1),
+            "elements_per_s": x.elements / (wall_3 * 1e-3),
+            "algorithmic_bytes": unf3_bytes, "hbm_GBps": round(unf3_bytes / (ev_3 * 1e-3) * 1e-9, 1),
+        }
         rec["fused_vs_unfused_speedup"] = round(ev_p / ev, 3)
+        rec["fused_vs_three_kernels_speedup"] = round(ev_3 / ev, 3)
         del S
     if with_attention and x.dtype == "bf16" and x.d in (64, 128) and x.N % 256 == 0:
         # the next step after the weights: O = P V with P kept on chip (nothing of size N^2 touches HBM)
@@ -348,6 +368,8 @@ def main() -> int:
         "cpu_baseline": cpu,
         "fused_vs_unfused_speedup": {k: v.get("fused_vs_unfused_speedup") for k, v in results.items()
                                      if "fused_vs_unfused_speedup" in v},
+        "fused_vs_three_kernels_speedup": {k: v.get("fused_vs_three_kernels_speedup") for k, v in results.items()
+                                           if "fused_vs_three_kernels_speedup" in v},
         "workloads": results,
     }
     print(json.dumps(line))

@@ -102,6 +102,21 @@ int attnw_gemm_scores(const void *Q, const void *K, void *S,
                       float scale, int dtype, void *stream);
 
 /*
+ * Scaling as a kernel of its own:  Y[i] = scale * X[i],  i < count, the exact
+ * product rounded once (to nearest even) to `dtype`.  With it the unfused
+ * pipeline can be run as the three kernels the paper's section "Fused Matrix
+ * Multiply + Scaling + Softmax" describes: attnw_gemm_scores with scale 1,
+ * attnw_scale, attnw_softmax, each reading and writing device memory.
+ *
+ * X : count elements, read only.          Y : count elements, written.
+ * count >= 1 arbitrary.  Y == X exactly (in place) is allowed; any other
+ * overlap is ATTNW_ERR_ALIAS.  Finite inputs whose products stay in the normal
+ * range of `dtype`.
+ */
+int attnw_scale(const void *X, void *Y, int64_t count, float scale,
+                int dtype, void *stream);
+
+/*
  * Attention output with the weights kept on chip (the product the paper's
  * Conclusion names as the next thing to fuse: Attention(Q, K, V) =
  * softmax(Q K^T / sqrt(d_k)) V, Multi-Head Self-Attention section):

@@ -46,6 +46,7 @@ def _load():
         lib.oracle_softmax.argtypes = [vp, ci, i64, i64, i64, i64, vp, ci]
         lib.oracle_attention_output.argtypes = [vp, vp, vp, ci, i64, i64, i64, cf, i64, i64, vp, vp, ci]
         lib.oracle_softmax_plain.argtypes = [vp, ci, i64, i64, vp]
+        lib.oracle_scale.argtypes = [vp, ci, i64, cf, vp]
         lib.oracle_threads_used.restype = ci
         _lib = lib
     return _lib
@@ -140,4 +141,13 @@ def softmax_plain(S: np.ndarray, dtype: str) -> np.ndarray:
     rc = _load().oracle_softmax_plain(S.ctypes.data, _DT[dtype], R, C, out.ctypes.data)
     if rc:
         raise ValueError("oracle_softmax_plain: bad arguments")
+    return out
+
+
+def scale(X: np.ndarray, dtype: str, scale) -> np.ndarray:
+    """The scaling step alone: fp64 ``scale * X`` (exact), same shape as X."""
+    X = _as(X, dtype)
+    out = np.empty(X.shape, dtype=np.float64)
+    if X.size and _load().oracle_scale(X.ctypes.data, _DT[dtype], X.size, float(np.float32(scale)), out.ctypes.data):
+        raise ValueError("oracle_scale: bad arguments")
     return out

@@ -16,7 +16,11 @@
  *     which has the same value and keeps exp() away from overflow;
  *   - the attention output  Attention(Q,K,V) = softmax(Q K^T / sqrt(d_k)) V
  *     (Multi-Head Self-Attention section; the paper's Conclusion names fusing
- *     this product into the kernel as the next step).
+ *     this product into the kernel as the next step);
+ *   - the scaling step on its own, scores divided by sqrt(d_k) as a separate
+ *     pass over the matrix (section "Fused Matrix Multiply + Scaling +
+ *     Softmax": the unfused pipeline runs multiply, scaling and softmax as
+ *     three kernels).
  *
  * Readings taken where the paper is silent (all listed in the design notes):
  * the scale is the fp32 number the caller hands to the library, widened
@@ -29,8 +33,10 @@
  * agreement of the plain definition with the max-subtracted form, and a
  * cross-check against scipy/numpy on small cases; for the attention output:
  * one-hot V (output = columns of P), constant V, Q = 0 (column means of V),
- * linearity in V, joint permutation of keys and values, the N = 2 closed form.
- * Nothing here is unpinned.
+ * linearity in V, joint permutation of keys and values, the N = 2 closed form;
+ * for the scaling step: hand-computed products, powers of two (exponent shift
+ * only), composition with the score oracle (scores at scale c = c * scores at
+ * scale 1), numpy.  Nothing here is unpinned.
  *
  * No blocking, fusion or reordering: every function is the definition, row by
  * row.  OpenMP only splits independent rows across host threads.
@@ -177,6 +183,20 @@ int oracle_softmax_plain(const void *S, int dtype, int64_t rows, int64_t cols, d
         for (int64_t j = 0; j < cols; ++j)
             out[j] = out[j] / l;
     }
+    return 0;
+}
+
+/*
+ * The scaling step alone:  Y_out[i] = scale * X[i]  in fp64 (exact: a 24-bit times an at most
+ * 24-bit significand), X in `dtype`, scale the fp32 number widened exactly.
+ */
+int oracle_scale(const void *X, int dtype, int64_t count, float scale, double *Y_out)
+{
+    if (!X || !Y_out || count < 1)
+        return -1;
+    const double c = (double)scale;
+    for (int64_t i = 0; i < count; ++i)
+        Y_out[i] = c * load_elem(X, dtype, i);
     return 0;
 }
 

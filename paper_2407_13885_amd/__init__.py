@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     attnw_attention,
     attnw_fused,
     attnw_gemm_scores,
+    attnw_scale,
     attnw_softmax,
     attnw_status_string,
     attnw_version,

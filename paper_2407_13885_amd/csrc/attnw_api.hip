@@ -109,6 +109,21 @@ int attnw_softmax(const void* S, void* P, int64_t rows, int64_t cols, int dtype,
     return e == hipSuccess ? ATTNW_OK : ATTNW_ERR_LAUNCH;
 }
 
+int attnw_scale(const void* X, void* Y, int64_t count, float scale, int dtype, void* stream)
+{
+    if (dtype != ATTNW_F32 && dtype != ATTNW_BF16) return ATTNW_ERR_DTYPE;
+    if (count < 0) return ATTNW_ERR_SHAPE;
+    if (count == 0) return ATTNW_OK;                          // empty problem
+    if (!X || !Y) return ATTNW_ERR_NULL;
+    int64_t bytes;
+    if (mul_overflows(count, elem_size(dtype), &bytes)) return ATTNW_ERR_SHAPE;
+    if (!aligned16(X) || !aligned16(Y)) return ATTNW_ERR_ALIGN;
+    if (X != Y && overlaps(Y, bytes, X, bytes)) return ATTNW_ERR_ALIAS;
+    const hipError_t e = attnw::launch_scale(static_cast<attnw::DType>(dtype), X, Y, count, scale,
+                                             static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? ATTNW_OK : ATTNW_ERR_LAUNCH;
+}
+
 const char* attnw_status_string(int status)
 {
     switch (status) {

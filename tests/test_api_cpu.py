@@ -122,6 +122,19 @@ def test_softmax_validation(lib):
     # S == P exactly (in place) passes validation; it is exercised on the GPU
 
 
+def test_scale_validation(lib):
+    s = lib.attnw_scale
+    assert s(QA, PA, 16, 0.5, 7, None) == E_DTYPE
+    assert s(QA, PA, -1, 0.5, BF16, None) == E_SHAPE
+    assert s(None, None, 0, 0.5, BF16, None) == OK
+    assert s(None, PA, 16, 0.5, BF16, None) == E_NULL
+    assert s(QA, None, 16, 0.5, F32, None) == E_NULL
+    assert s(QA, PA, 1 << 62, 0.5, F32, None) == E_SHAPE
+    assert s(QA + 2, PA, 16, 0.5, BF16, None) == E_ALIGN
+    assert s(QA, QA + 16, 16, 0.5, BF16, None) == E_ALIAS       # partial overlap
+    # X == Y exactly (in place) passes validation; it is exercised on the GPU
+
+
 def test_binding_raises_with_status(lib):
     with pytest.raises(binding.AttnwError) as ei:
         binding.attnw_softmax(QA + 1, PA, 4, 4, BF16)

@@ -1,0 +1,131 @@
+"""GPU parity of the scaling kernel and of the three-kernel pipeline (matrix multiply, scaling,
+softmax as separate kernels: what the paper's fused kernel replaces).
+
+The scaling step has exactly one correct result per element - the exact product rounded once to
+the storage type - so it is compared bit for bit with the oracle's fp64 product rounded here."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2407_13885_amd as attnw
+from paper_2407_13885_amd import workloads as wl
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _gpu():
+    gu.require_gpu()
+
+
+def round_once(y64: np.ndarray, dtype: str) -> np.ndarray:
+    """fp64 -> storage bits with ONE rounding to nearest even (normal-range values)."""
+    if dtype == "f32":
+        return y64.astype(np.float32).view(np.uint32)
+    u = np.ascontiguousarray(y64, dtype=np.float64).view(np.uint64)
+    drop = np.uint64(45)                                   # 52 stored significand bits -> 7
+    bias = ((u >> drop) & np.uint64(1)) + np.uint64((1 << 44) - 1)
+    r = ((u + bias) >> drop) << drop
+    return (r.view(np.float64).astype(np.float32).view(np.uint32) >> np.uint32(16)).astype(np.uint16)
+
+
+def bits_of(t: torch.Tensor, dtype: str) -> np.ndarray:
+    if dtype == "f32":
+        return t.cpu().numpy().view(np.uint32)
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def run_scale(x_store: np.ndarray, dtype: str, scale: float, inplace: bool = False, guard: int = 1024):
+    X = gu.to_dev(x_store.reshape(-1), dtype)
+    n = X.numel()
+    if inplace:
+        attnw.attnw_scale(X, X, n, scale, gu.DT[dtype])
+        torch.cuda.synchronize()
+        return X
+    Y, canary = gu.empty_like_out((n,), dtype, guard)
+    attnw.attnw_scale(X, Y, n, scale, gu.DT[dtype])
+    torch.cuda.synchronize()
+    assert gu.guards_intact(canary), "scale kernel wrote outside Y"
+    assert np.array_equal(bits_of(X, dtype), x_store.reshape(-1).view(bits_of(X, dtype).dtype)), "input modified"
+    return Y
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("count", [1, 7, 8, 9, 1023, 4096, 1000003, 1 << 22])
+def test_scale_bit_exact_any_count(dtype, count):
+    x = wl.store(wl.standard_normal(900 + count % 97, 2, count) * 3.0, dtype)
+    scale = float(np.float32(1.0 / math.sqrt(128.0)))
+    ref = round_once(oracle.scale(x, dtype, scale), dtype)
+    assert np.array_equal(bits_of(run_scale(x, dtype, scale), dtype), ref)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("scale", [0.125, -0.37, 3.0, 1.0, 0.0])
+def test_scale_values_and_in_place(dtype, scale):
+    x = wl.store(wl.standard_normal(41, 2, 70001) * 5.0, dtype)
+    ref = round_once(oracle.scale(x, dtype, scale), dtype)
+    got = bits_of(run_scale(x, dtype, scale), dtype)
+    got_in_place = bits_of(run_scale(x, dtype, scale, inplace=True), dtype)
+    assert np.array_equal(got, ref)
+    assert np.array_equal(got_in_place, ref)
+
+
+def test_scale_bf16_products_that_round_to_a_tie_in_fp32():
+    """Products whose fp32 rounding lands exactly half way between two bf16 values although the
+    exact product does not: rounding twice would go to the even neighbour, the exact product
+    decides otherwise in half of the cases."""
+    r = np.random.default_rng(12345)
+    scales = (r.uniform(0.05, 4.0, 4096)).astype(np.float32)
+    xs = wl.store(r.uniform(0.5, 8.0, 512) * r.choice([-1.0, 1.0], 512), "bf16")
+    xw = wl.widen(xs, "bf16")
+    exact = scales.astype(np.float64)[:, None] * xw[None, :]
+    f32 = exact.astype(np.float32)
+    tie = ((f32.view(np.uint32) & np.uint32(0xFFFF)) == np.uint32(0x8000)) & (f32.astype(np.float64) != exact)
+    si, xi = np.nonzero(tie)
+    assert len(si) >= 8, "search found too few cases"
+    differs = 0
+    for a, b in list(zip(si, xi))[:24]:
+        x1 = xs[b:b + 1]
+        ref = round_once(oracle.scale(x1, "bf16", float(scales[a])), "bf16")
+        twice = wl.f32_to_bf16_bits(f32[a, b:b + 1])
+        differs += int(ref[0] != twice[0])
+        got = bits_of(run_scale(x1, "bf16", float(scales[a]), guard=64), "bf16")
+        assert got[0] == ref[0], (float(scales[a]), float(xw[b]), hex(int(got[0])), hex(int(ref[0])))
+    assert differs >= 1, "none of the cases tells single from double rounding"
+
+
+@pytest.mark.parametrize("dtype,N,d", [("bf16", 512, 64), ("bf16", 320, 128), ("f32", 200, 64)])
+def test_three_kernel_pipeline_stage_by_stage(dtype, N, d):
+    """gemm_scores at scale 1, attnw_scale in place, attnw_softmax: each stage against the oracle on
+    the input that stage actually received."""
+    H = 2
+    scale = float(np.float32(1.0 / math.sqrt(d)))
+    x = wl.fused_inputs("t", dtype, 1, H, N, d, seed=1200 + N, scale=1.0)
+    S = gu.run_scores(x, guard=4096)
+    got = gu.to_f64(S)
+    Qa, Ka = np.abs(wl.widen(x.Q, dtype)), np.abs(wl.widen(x.K, dtype))
+    for h in range(H):
+        ref = oracle.scores(x.Q[0, h], x.K[0, h], dtype, 1.0)
+        acc_bound = d * 2.0 ** -24 * (Qa[0, h] @ Ka[0, h].T)
+        store = (2.0 ** -8 if dtype == "bf16" else 2.0 ** -24) * np.abs(ref)
+        assert (np.abs(got[0, h] - ref) <= acc_bound + store + 1e-30).all(), f"unscaled scores {dtype} head {h}"
+    s_store = bits_of(S.reshape(-1), dtype)
+    s_store = s_store.view(np.float32) if dtype == "f32" else s_store
+    attnw.attnw_scale(S, S, S.numel(), scale, gu.DT[dtype])
+    torch.cuda.synchronize()
+    assert np.array_equal(bits_of(S.reshape(-1), dtype), round_once(oracle.scale(s_store, dtype, scale), dtype))
+    scaled = bits_of(S.reshape(-1), dtype)
+    scaled = (scaled.view(np.float32) if dtype == "f32" else scaled).reshape(H * N, N)
+    P = gu.run_softmax(S.view(H * N, N), H * N, N, dtype)
+    gu.check_weights(gu.to_f64(P), oracle.softmax(scaled, dtype), dtype, f"three-kernel softmax {dtype}")
+    # end to end against the weights of the exact scores: reported precision of the unfused path
+    # (bf16 scores rounded twice on the way cannot meet the fused tolerance; fp32 does)
+    if dtype == "f32":
+        ref_p = oracle.attention_weights_bh(x.Q, x.K, dtype, scale)
+        gu.check_weights(gu.to_f64(P).reshape(1, H, N, N), ref_p, dtype, "three-kernel end to end fp32",
+                         abs_f32=2e-6)

@@ -290,3 +290,31 @@ def test_output_against_numpy_scipy(n, d, dv):
     assert np.array_equal(P, oracle.attention_weights(Q, K, "f64", c))
     rows = oracle.attention_output(Q, K, V, "f64", c, rows=(n // 2, n))
     assert np.array_equal(rows, got[n // 2:])
+
+
+# ---- the scaling step on its own (section "Fused Matrix Multiply + Scaling + Softmax") -------------
+
+def test_scale_hand_values_and_powers_of_two():
+    x = np.array([1.5, -2.25, 0.1, 0.0], dtype=np.float32)
+    got = oracle.scale(x, "f32", 3.0)
+    assert got.tolist() == [4.5, -6.75, 3.0 * float(np.float32(0.1)), 0.0]
+    r = _rng(5)
+    xb = wl.store(r.standard_normal(1000) * 4.0, "bf16")
+    got = oracle.scale(xb, "bf16", 0.125)
+    assert np.array_equal(got, np.ldexp(wl.widen(xb, "bf16"), -3))           # exponent shift only
+    assert np.array_equal(oracle.scale(xb, "bf16", 1.0), wl.widen(xb, "bf16"))
+    assert np.array_equal(oracle.scale(xb, "bf16", -1.0), -wl.widen(xb, "bf16"))
+
+
+def test_scale_uses_the_fp32_scale_and_matches_numpy_and_the_score_oracle():
+    r = _rng(6)
+    x = wl.store(r.standard_normal((7, 33)), "f32")
+    c = 1.0 / math.sqrt(128.0)
+    got = oracle.scale(x, "f32", c)
+    assert got.shape == x.shape
+    assert np.array_equal(got, float(np.float32(c)) * x.astype(np.float64))
+    assert not np.array_equal(got, c * x.astype(np.float64))                 # the double 1/sqrt(128) is another number
+    # scores at scale c are c times the scores at scale 1
+    Q, K = wl.store(r.standard_normal((9, 16)), "bf16"), wl.store(r.standard_normal((9, 16)), "bf16")
+    s1 = oracle.scores(Q, K, "bf16", 1.0)
+    np.testing.assert_allclose(oracle.scale(s1, "f64", c), oracle.scores(Q, K, "bf16", c), rtol=1e-15, atol=0)
