@@ -3,9 +3,9 @@
 // The paper's Conclusion names the product with V as the next thing to fuse into its kernel
 // (Multi-Head Self-Attention section: Attention(Q, K, V) = softmax(Q K^T / sqrt(d_k)) V).  Once the
 // weights are not written, nothing forces two sweeps over the keys: the max-subtracted softmax
-// (Softmax section, Eq. 1) is applied incrementally -- a running row maximum m and sum l, and an
-// output accumulator that is rescaled by 2^(c m_old - c m_new) whenever the maximum grows -- and
-// one sweep over the K and V tiles suffices.
+// (Softmax section, Eq. 1) is applied incrementally -- a reference exponent that follows the running
+// row maximum, a running sum l, and an output accumulator that is rescaled by 2^(old - new) whenever
+// the reference moves -- and one sweep over the K and V tiles suffices.
 //
 // Work split: one workgroup of 8 waves per (head, strip of 8 * QW queries); every wave owns
 // QW = 32 * QB queries and walks ALL keys, so no statistics cross waves.  Per 128-key tile:
@@ -14,7 +14,7 @@
 //           keys, and a matrix-core operand wants its 8 contraction elements contiguous per lane.
 // Per 32-key sub-tile and query block (all on v_mfma_f32_32x32x16_bf16, fp32 accumulate):
 //   S^T = K_sub * Q^T          lane (query l32, half h) holds keys 8i + 4h + j of its query;
-//   running max (shared by lanes l, l+32: both feed the same second contraction), p = 2^(c s - c m),
+//   sub-tile max (shared by lanes l, l+32: both feed the same second contraction), p = 2^(c s - ref),
 //   l += sum p (fp32), p rounded to bf16;
 //   O^T += Vt_sub * P^T        lane (query l32, half h) holds O[query][8i + 4h + j] per 32-wide block.
 // The k-index of the second contraction is a permutation of the keys chosen so that a lane's own
@@ -170,10 +170,11 @@ void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
     };
 
     f32x16 oacc[QB][DVB];
-    float mb_run[QB], m_run[QB], l_run[QB];
+    float mb_run[QB], l_run[QB];
+    constexpr float kLazy = 8.0f;    // binades the maximum may run ahead of the reference exponent
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-        mb_run[qb] = kNegBig; m_run[qb] = kNegBig; l_run[qb] = 0.0f;
+        mb_run[qb] = kNegBig; l_run[qb] = 0.0f;
 #pragma unroll
         for (int b = 0; b < DVB; ++b)
 #pragma unroll
@@ -206,23 +207,26 @@ void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
                     vf[b][m] = *reinterpret_cast<const u32x4*>(vb + b * 32 * VT_PITCH + (u * 32 + 16 * m) * 2);
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb) {
-                // running maximum, shared by the two lanes of a query
+                // maximum of this sub-tile, shared by the two lanes of a query
                 float tm = max3(s[qb][0], s[qb][1], s[qb][2]);
 #pragma unroll
                 for (int r = 3; r < 15; r += 2) tm = max3(tm, s[qb][r], s[qb][r + 1]);
-                const float mn = half_max(max3(tm, s[qb][15], m_run[qb]));
-                m_run[qb] = mn;
-                const float mbn = mn * c;
-                // Rescale only when some query of the wave saw its maximum grow (rare after the first tiles).
-                // Lanes whose maximum stands get the factor 2^0 = 1 exactly.
-                if (__builtin_amdgcn_ballot_w64(mbn > mb_run[qb]) != 0) {
-                    const float alpha = fast_exp2(mb_run[qb] - mbn);
+                const float mbn = half_max(fmaxf(tm, s[qb][15])) * c;
+                // The exponent the weights are taken against (mb_run) follows the running maximum lazily:
+                // it moves only when some query of the wave exceeds it by more than kLazy binades.  Until
+                // then weights up to 2^kLazy appear, which costs nothing (fp32 sums, and bf16 has the same
+                // relative precision at every magnitude), and the 16 * DVB multiplies of the output
+                // accumulator - needed at every new maximum otherwise, i.e. in most of the early sub-tiles
+                // of a row - become rare.  Lanes whose exponent stands get the factor 2^0 = 1 exactly.
+                if (__builtin_amdgcn_ballot_w64(mbn > mb_run[qb] + kLazy) != 0) {
+                    const float mb_new = fmaxf(mb_run[qb], mbn);
+                    const float alpha = fast_exp2(mb_run[qb] - mb_new);
                     l_run[qb] *= alpha;
 #pragma unroll
                     for (int b = 0; b < DVB; ++b)
 #pragma unroll
                         for (int r = 0; r < 16; ++r) oacc[qb][b][r] *= alpha;
-                    mb_run[qb] = mbn;
+                    mb_run[qb] = mb_new;
                 }
                 const float mb = mb_run[qb];
                 float p[16];

@@ -95,6 +95,31 @@ def test_attention_full_size_sampled_rows(name):
         _check_rows(O[0, h], x, V, 0, h, rows, f"{name} attention head {h}")
 
 
+@pytest.mark.parametrize("d,step", [(64, 0.02), (128, 0.02), (64, 0.4), (128, 0.25)])
+def test_attention_scores_climbing_along_the_keys(d, step):
+    """Scores that grow with the key index: every sub-tile brings a new row maximum.  Small steps stay
+    inside the window in which the kernel keeps its reference exponent (weights above 1 appear), large
+    steps (8 and more nats per 32 keys) force the reference to move at every sub-tile; the last keys
+    carry all the weight.  Scores stay within a few hundred: the fp32 score arithmetic resolves
+    differences of scores only to 2^-24 of their magnitude."""
+    N = 1024
+    x = wl.fused_inputs("t", "bf16", 1, 2, N, d, seed=90 + d)
+    # q = e_0 * a (plus noise in the other coordinates), k_j[0] = j * step / (a * scale): score ~ j * step
+    a = 4.0
+    ramp = (np.arange(N, dtype=np.float64) * step / (a * float(x.scale)))
+    Kw = wl.widen(x.K, "bf16") * 0.05
+    Kw[..., 0] = ramp[None, None, :]
+    Qw = wl.widen(x.Q, "bf16") * 0.05
+    Qw[..., 0] = a
+    Qw[0, 1, ::2, 0] = -a            # every other query of head 1 sees the scores fall instead
+    x.Q[...] = wl.store(Qw, "bf16")
+    x.K[...] = wl.store(Kw, "bf16")
+    V = wl.value_inputs(x, seed=91 + d)
+    O = gu.to_f64(_run(x, V))
+    for h in range(2):
+        _check_rows(O[0, h], x, V, 0, h, (0, N), f"climbing scores d={d} step={step} head {h}")
+
+
 def test_attention_is_deterministic():
     x = wl.fused_inputs("t", "bf16", 1, 2, 512, 64, seed=6)
     V = wl.value_inputs(x, seed=7)
