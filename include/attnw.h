@@ -91,6 +91,19 @@ int attnw_softmax(const void *S, void *P, int64_t rows, int64_t cols,
                   int dtype, void *stream);
 
 /*
+ * The same row softmax with separate storage types for scores and weights
+ * (e.g. fp32 scores in, bf16 weights out: 6 instead of 8 bytes of device
+ * memory traffic per element, one rounding of the result).  The arithmetic in
+ * between is fp32 whatever the types.
+ *
+ * S : [rows][cols] in `in_dtype`, read only.   P : [rows][cols] in `out_dtype`.
+ * With in_dtype == out_dtype this is attnw_softmax (in place allowed); with
+ * different types P must not overlap S at all.
+ */
+int attnw_softmax_cast(const void *S, void *P, int64_t rows, int64_t cols,
+                       int in_dtype, int out_dtype, void *stream);
+
+/*
  * First half of the unfused pair (matrix multiply + scaling as its own kernel,
  * scores round-trip through device memory -- the pipeline the paper's fused
  * kernel replaces):  S[b][h][i][j] = scale * sum_t Q[b][h][i][t] * K[b][h][j][t],

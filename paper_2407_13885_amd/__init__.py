@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     attnw_gemm_scores,
     attnw_scale,
     attnw_softmax,
+    attnw_softmax_cast,
     attnw_status_string,
     attnw_version,
     build,

@@ -22,7 +22,7 @@ _ROOT = os.path.dirname(_PKG)
 _CSRC = os.path.join(_PKG, "csrc")
 _LIB = os.path.join(_PKG, "libattnw.so")
 
-EXPORTS = ("attnw_fused", "attnw_softmax", "attnw_gemm_scores", "attnw_scale", "attnw_attention",
+EXPORTS = ("attnw_fused", "attnw_softmax", "attnw_softmax_cast", "attnw_gemm_scores", "attnw_scale", "attnw_attention",
            "attnw_status_string", "attnw_version")
 
 HIPCC_FLAGS = [
@@ -79,6 +79,8 @@ def load_library():
         lib.attnw_attention.restype = ci
         lib.attnw_softmax.argtypes = [vp, vp, i64, i64, ci, vp]
         lib.attnw_softmax.restype = ci
+        lib.attnw_softmax_cast.argtypes = [vp, vp, i64, i64, ci, ci, vp]
+        lib.attnw_softmax_cast.restype = ci
         lib.attnw_scale.argtypes = [vp, vp, i64, ctypes.c_float, ci, vp]
         lib.attnw_scale.restype = ci
         lib.attnw_status_string.argtypes = [ci]
@@ -127,6 +129,12 @@ def attnw_fused(Q, K, P, B: int, H: int, N: int, d: int, scale: float, dtype: in
 def attnw_softmax(S, P, rows: int, cols: int, dtype: int, stream=None) -> None:
     """Row softmax of S into P; see ``attnw_softmax`` in include/attnw.h."""
     _check(load_library().attnw_softmax(_ptr(S), _ptr(P), rows, cols, int(dtype), _stream(stream)))
+
+
+def attnw_softmax_cast(S, P, rows: int, cols: int, in_dtype: int, out_dtype: int, stream=None) -> None:
+    """Row softmax with separate input and output types; see ``attnw_softmax_cast`` in include/attnw.h."""
+    _check(load_library().attnw_softmax_cast(_ptr(S), _ptr(P), rows, cols, int(in_dtype), int(out_dtype),
+                                             _stream(stream)))
 
 
 def attnw_scale(X, Y, count: int, scale: float, dtype: int, stream=None) -> None:

@@ -91,22 +91,37 @@ int attnw_attention(const void* Q, const void* K, const void* V, void* O, int64_
     return e == hipSuccess ? ATTNW_OK : ATTNW_ERR_LAUNCH;
 }
 
-int attnw_softmax(const void* S, void* P, int64_t rows, int64_t cols, int dtype, void* stream)
+// Shared by attnw_softmax and attnw_softmax_cast.
+static int run_softmax(const void* S, void* P, int64_t rows, int64_t cols, int in_dtype, int out_dtype, void* stream)
 {
-    if (dtype != ATTNW_F32 && dtype != ATTNW_BF16) return ATTNW_ERR_DTYPE;
+    if (in_dtype != ATTNW_F32 && in_dtype != ATTNW_BF16) return ATTNW_ERR_DTYPE;
+    if (out_dtype != ATTNW_F32 && out_dtype != ATTNW_BF16) return ATTNW_ERR_DTYPE;
     if (rows < 0 || cols < 0) return ATTNW_ERR_SHAPE;
     if (rows == 0 || cols == 0) return ATTNW_OK;              // empty problem
     if (!S || !P) return ATTNW_ERR_NULL;
-    int64_t elems, bytes;
-    if (mul_overflows(rows, cols, &elems) || mul_overflows(elems, elem_size(dtype), &bytes)) return ATTNW_ERR_SHAPE;
+    int64_t elems, in_bytes, out_bytes;
+    if (mul_overflows(rows, cols, &elems) || mul_overflows(elems, elem_size(in_dtype), &in_bytes) ||
+        mul_overflows(elems, elem_size(out_dtype), &out_bytes))
+        return ATTNW_ERR_SHAPE;
     // one workgroup per row (or per four rows): the grid's x extent is 32-bit
     if (rows > (int64_t)std::numeric_limits<int32_t>::max()) return ATTNW_ERR_UNSUPPORTED;
     if (!aligned16(S) || !aligned16(P)) return ATTNW_ERR_ALIGN;
-    if (S != P && overlaps(P, bytes, S, bytes)) return ATTNW_ERR_ALIAS;
+    // in place only when every element is read and written at the same address
+    if (!(S == P && in_dtype == out_dtype) && overlaps(P, out_bytes, S, in_bytes)) return ATTNW_ERR_ALIAS;
 
-    const hipError_t e = attnw::launch_softmax(static_cast<attnw::DType>(dtype), S, P, rows, cols,
-                                               static_cast<hipStream_t>(stream));
+    const hipError_t e = attnw::launch_softmax(static_cast<attnw::DType>(in_dtype), static_cast<attnw::DType>(out_dtype),
+                                               S, P, rows, cols, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? ATTNW_OK : ATTNW_ERR_LAUNCH;
+}
+
+int attnw_softmax(const void* S, void* P, int64_t rows, int64_t cols, int dtype, void* stream)
+{
+    return run_softmax(S, P, rows, cols, dtype, dtype, stream);
+}
+
+int attnw_softmax_cast(const void* S, void* P, int64_t rows, int64_t cols, int in_dtype, int out_dtype, void* stream)
+{
+    return run_softmax(S, P, rows, cols, in_dtype, out_dtype, stream);
 }
 
 int attnw_scale(const void* X, void* Y, int64_t count, float scale, int dtype, void* stream)

@@ -9,7 +9,7 @@ namespace attnw {
 enum class DType : int { F32 = 0, BF16 = 1 };
 
 // Row softmax, arguments already validated.  Returns the launch status.
-hipError_t launch_softmax(DType dt, const void* S, void* P, int64_t rows, int64_t cols, hipStream_t stream);
+hipError_t launch_softmax(DType in, DType out, const void* S, void* P, int64_t rows, int64_t cols, hipStream_t stream);
 
 // Fused attention weights (scores_only = false) or scaled scores (scores_only = true).
 hipError_t launch_qk(DType dt, bool scores_only, const void* Q, const void* K, void* out,

@@ -52,43 +52,50 @@ template <> struct Elem<uint16_t> {   // bf16 bit patterns
     static __device__ __forceinline__ void store1(uint16_t* p, float v) { *p = (uint16_t)(pack_bf16x2(v, 0.0f) & 0xffffu); }
 };
 
-// One row per TPR threads; every thread keeps R 16-byte chunks of the row in
-// registers.  TPR == 64: four rows per 256-thread block, wave-local reductions
-// only.  TPR > 64: one row per block, partial results meet in LDS.
-// Requires cols to be a multiple of VEC (chunks = cols / VEC <= R * TPR).
-template <typename T, int R, int TPR>
+// One row per TPR threads; every thread keeps R groups of E elements of the row in registers
+// (E = the larger of the two types' elements per 16-byte chunk: a group is one chunk of the
+// narrower type and one or two of the wider).  TPR == 64: four rows per 256-thread block,
+// wave-local reductions only.  TPR > 64: one row per block, partial results meet in LDS.
+// Requires cols to be a multiple of E (groups = cols / E <= R * TPR).
+template <typename TI, typename TO, int R, int TPR>
 __global__ __launch_bounds__(TPR == 64 ? 256 : TPR)
-void softmax_rows_kernel(const T* S, T* P, int64_t rows, int chunks)   // S == P (in place) is allowed
+void softmax_rows_kernel(const TI* S, TO* P, int64_t rows, int groups)   // S == P (in place, TI == TO) is allowed
 {
-    constexpr int VEC = Elem<T>::VEC;
+    constexpr int VI = Elem<TI>::VEC, VO = Elem<TO>::VEC;
+    constexpr int E = VI > VO ? VI : VO;
+    constexpr int CI = E / VI, CO = E / VO;     // 16-byte chunks per group on the way in / out
     constexpr int WAVES = (TPR == 64) ? 1 : TPR / 64;
     const int tid = (TPR == 64) ? (int)(threadIdx.x & 63) : (int)threadIdx.x;
     const int64_t row = (TPR == 64) ? (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6) : (int64_t)blockIdx.x;
     if (row >= rows) return;   // whole wave (TPR == 64) or whole block leaves together
 
-    const u32x4* src = reinterpret_cast<const u32x4*>(S) + row * chunks;
-    u32x4* dst = reinterpret_cast<u32x4*>(P) + row * chunks;
+    const u32x4* src = reinterpret_cast<const u32x4*>(S) + row * groups * CI;
+    u32x4* dst = reinterpret_cast<u32x4*>(P) + row * groups * CO;
 
-    u32x4 raw[R];
+    u32x4 raw[R][CI];
 #pragma unroll
     for (int k = 0; k < R; ++k) {
         const int c = tid + k * TPR;
-        if (c < chunks) raw[k] = __builtin_nontemporal_load(src + c);
+        if (c < groups) {
+#pragma unroll
+            for (int j = 0; j < CI; ++j) raw[k][j] = __builtin_nontemporal_load(src + c * CI + j);
+        }
     }
 
-    float x[R][VEC];
+    float x[R][E];
     float m = -INFINITY;
 #pragma unroll
     for (int k = 0; k < R; ++k) {
         const int c = tid + k * TPR;
-        if (c < chunks) {
-            Elem<T>::unpack(raw[k], x[k]);
+        if (c < groups) {
+#pragma unroll
+            for (int j = 0; j < CI; ++j) Elem<TI>::unpack(raw[k][j], x[k] + j * VI);
         } else {
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) x[k][i] = -INFINITY;
+            for (int i = 0; i < E; ++i) x[k][i] = -INFINITY;
         }
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) m = fmaxf(m, x[k][i]);
+        for (int i = 0; i < E; ++i) m = fmaxf(m, x[k][i]);
     }
 
     __shared__ float red[2][WAVES];
@@ -106,7 +113,7 @@ void softmax_rows_kernel(const T* S, T* P, int64_t rows, int chunks)   // S == P
 #pragma unroll
     for (int k = 0; k < R; ++k) {
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) {
+        for (int i = 0; i < E; ++i) {
             x[k][i] = fast_exp2((x[k][i] - m) * kLog2e);
             l += x[k][i];
         }
@@ -124,29 +131,30 @@ void softmax_rows_kernel(const T* S, T* P, int64_t rows, int chunks)   // S == P
 #pragma unroll
     for (int k = 0; k < R; ++k) {
         const int c = tid + k * TPR;
-        if (c < chunks) {
+        if (c < groups) {
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) x[k][i] *= inv;
-            __builtin_nontemporal_store(Elem<T>::pack(x[k]), dst + c);
+            for (int i = 0; i < E; ++i) x[k][i] *= inv;
+#pragma unroll
+            for (int j = 0; j < CO; ++j) __builtin_nontemporal_store(Elem<TO>::pack(x[k] + j * VO), dst + c * CO + j);
         }
     }
 }
 
 // Any cols (ragged, unaligned rows, rows too long for registers): one row per
 // 256-thread block, element-wise accesses, the row is read twice.
-template <typename T>
+template <typename TI, typename TO>
 __global__ __launch_bounds__(256)
-void softmax_generic_kernel(const T* S, T* P, int64_t rows, int64_t cols)
+void softmax_generic_kernel(const TI* S, TO* P, int64_t rows, int64_t cols)
 {
     const int64_t row = blockIdx.x;
     if (row >= rows) return;
-    const T* src = S + row * cols;
-    T* dst = P + row * cols;
+    const TI* src = S + row * cols;
+    TO* dst = P + row * cols;
 
     // online (max, sum): after folding x, l = sum exp(x_k - m) over the k seen so far
     float m = kNegBig, l = 0.0f;
     for (int64_t j = threadIdx.x; j < cols; j += 256) {
-        const float x = Elem<T>::load1(src + j);
+        const float x = Elem<TI>::load1(src + j);
         const float mn = fmaxf(m, x);
         l = l * fast_exp2((m - mn) * kLog2e) + fast_exp2((x - mn) * kLog2e);
         m = mn;
@@ -168,50 +176,53 @@ void softmax_generic_kernel(const T* S, T* P, int64_t rows, int64_t cols)
     for (int w = 0; w < 4; ++w) l += sl[w] * fast_exp2((sm[w] - m) * kLog2e);
     const float inv = 1.0f / l;
     for (int64_t j = threadIdx.x; j < cols; j += 256) {
-        const float x = Elem<T>::load1(src + j);
-        Elem<T>::store1(dst + j, fast_exp2((x - m) * kLog2e) * inv);
+        const float x = Elem<TI>::load1(src + j);
+        Elem<TO>::store1(dst + j, fast_exp2((x - m) * kLog2e) * inv);
     }
 }
 
-template <typename T, int R, int TPR>
-hipError_t launch_rows(const void* S, void* P, int64_t rows, int chunks, hipStream_t stream)
+template <typename TI, typename TO, int R, int TPR>
+hipError_t launch_rows(const void* S, void* P, int64_t rows, int groups, hipStream_t stream)
 {
     const int64_t blocks = (TPR == 64) ? (rows + 3) / 4 : rows;
     const int threads = (TPR == 64) ? 256 : TPR;
-    hipLaunchKernelGGL((softmax_rows_kernel<T, R, TPR>), dim3((uint32_t)blocks), dim3(threads), 0, stream,
-                       static_cast<const T*>(S), static_cast<T*>(P), rows, chunks);
+    hipLaunchKernelGGL((softmax_rows_kernel<TI, TO, R, TPR>), dim3((uint32_t)blocks), dim3(threads), 0, stream,
+                       static_cast<const TI*>(S), static_cast<TO*>(P), rows, groups);
     return hipGetLastError();
 }
 
-template <typename T>
+template <typename TI, typename TO>
 hipError_t launch_softmax_t(const void* S, void* P, int64_t rows, int64_t cols, hipStream_t stream)
 {
-    constexpr int VEC = Elem<T>::VEC;
-    // Register-resident rows: up to 8 chunks per thread for bf16, 4 for fp32 (a
-    // thread's chunk is 8 resp. 4 fp32 values once unpacked).
-    constexpr int MAXR = (sizeof(T) == 4) ? 4 : 8;
-    if (cols % VEC == 0 && cols / VEC <= 1024 * MAXR) {
-        const int chunks = (int)(cols / VEC);
-        if (chunks <= 64) return launch_rows<T, 1, 64>(S, P, rows, chunks, stream);
-        if (chunks <= 128) return launch_rows<T, 2, 64>(S, P, rows, chunks, stream);
-        if (chunks <= 256) return launch_rows<T, 4, 64>(S, P, rows, chunks, stream);
-        if (chunks <= 512) return launch_rows<T, 2, 256>(S, P, rows, chunks, stream);
-        if (chunks <= 1024) return launch_rows<T, 4, 256>(S, P, rows, chunks, stream);
-        if (chunks <= 2048) return launch_rows<T, 2, 1024>(S, P, rows, chunks, stream);
-        if (chunks <= 4096) return launch_rows<T, 4, 1024>(S, P, rows, chunks, stream);
-        if constexpr (MAXR >= 8) return launch_rows<T, 8, 1024>(S, P, rows, chunks, stream);
+    constexpr int E = Elem<TI>::VEC > Elem<TO>::VEC ? Elem<TI>::VEC : Elem<TO>::VEC;
+    // Register-resident rows: up to 8 groups per thread when a group is 8 elements, 4 when both
+    // types are fp32 (a thread's group is 8 resp. 4 fp32 values once unpacked).
+    constexpr int MAXR = (E == 4) ? 4 : 8;
+    if (cols % E == 0 && cols / E <= 1024 * MAXR) {
+        const int groups = (int)(cols / E);
+        if (groups <= 64) return launch_rows<TI, TO, 1, 64>(S, P, rows, groups, stream);
+        if (groups <= 128) return launch_rows<TI, TO, 2, 64>(S, P, rows, groups, stream);
+        if (groups <= 256) return launch_rows<TI, TO, 4, 64>(S, P, rows, groups, stream);
+        if (groups <= 512) return launch_rows<TI, TO, 2, 256>(S, P, rows, groups, stream);
+        if (groups <= 1024) return launch_rows<TI, TO, 4, 256>(S, P, rows, groups, stream);
+        if (groups <= 2048) return launch_rows<TI, TO, 2, 1024>(S, P, rows, groups, stream);
+        if (groups <= 4096) return launch_rows<TI, TO, 4, 1024>(S, P, rows, groups, stream);
+        if constexpr (MAXR >= 8) return launch_rows<TI, TO, 8, 1024>(S, P, rows, groups, stream);
     }
-    hipLaunchKernelGGL((softmax_generic_kernel<T>), dim3((uint32_t)rows), dim3(256), 0, stream,
-                       static_cast<const T*>(S), static_cast<T*>(P), rows, cols);
+    hipLaunchKernelGGL((softmax_generic_kernel<TI, TO>), dim3((uint32_t)rows), dim3(256), 0, stream,
+                       static_cast<const TI*>(S), static_cast<TO*>(P), rows, cols);
     return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_softmax(DType dt, const void* S, void* P, int64_t rows, int64_t cols, hipStream_t stream)
+hipError_t launch_softmax(DType in, DType out, const void* S, void* P, int64_t rows, int64_t cols, hipStream_t stream)
 {
-    if (dt == DType::F32) return launch_softmax_t<float>(S, P, rows, cols, stream);
-    return launch_softmax_t<uint16_t>(S, P, rows, cols, stream);
+    if (in == DType::F32)
+        return out == DType::F32 ? launch_softmax_t<float, float>(S, P, rows, cols, stream)
+                                 : launch_softmax_t<float, uint16_t>(S, P, rows, cols, stream);
+    return out == DType::F32 ? launch_softmax_t<uint16_t, float>(S, P, rows, cols, stream)
+                             : launch_softmax_t<uint16_t, uint16_t>(S, P, rows, cols, stream);
 }
 
 }  // namespace attnw

@@ -122,6 +122,19 @@ def test_softmax_validation(lib):
     # S == P exactly (in place) passes validation; it is exercised on the GPU
 
 
+def test_softmax_cast_validation(lib):
+    s = lib.attnw_softmax_cast
+    assert s(QA, PA, 4, 8, 5, BF16, None) == E_DTYPE
+    assert s(QA, PA, 4, 8, F32, -2, None) == E_DTYPE
+    assert s(QA, PA, -4, 8, F32, BF16, None) == E_SHAPE
+    assert s(None, None, 0, 8, F32, BF16, None) == OK
+    assert s(None, PA, 4, 8, F32, BF16, None) == E_NULL
+    assert s(QA, PA + 4, 4, 8, F32, BF16, None) == E_ALIGN
+    assert s(QA, QA, 4, 8, F32, BF16, None) == E_ALIAS            # in place needs equal types
+    assert s(QA, QA + 64, 4, 8, F32, BF16, None) == E_ALIAS       # bf16 output inside the fp32 input
+    assert s(QA, QA + 128, 4, 8, F32, BF16, None) != E_ALIAS      # directly behind it: no overlap
+
+
 def test_scale_validation(lib):
     s = lib.attnw_scale
     assert s(QA, PA, 16, 0.5, 7, None) == E_DTYPE

@@ -85,6 +85,38 @@ def test_c4_unfused_pair_full_size():
                          f"unfused softmax head {h}")
 
 
+@pytest.mark.parametrize("name", ["c3", "c4"])
+def test_three_kernel_pipeline_full_size(name):
+    """Multiply (scale 1), scaling in place, softmax at benchmark sizes: the scaling stage bit for bit on
+    sampled rows (first, last and interior blocks of the flat array included), the softmax against the
+    oracle softmax of the scaled scores actually produced."""
+    import paper_2407_13885_amd as attnw
+    x = wl.CONFIGS[name]()
+    scale = float(x.scale)
+    Q, K = gu.to_dev(x.Q, "bf16"), gu.to_dev(x.K, "bf16")
+    S = torch.empty((x.B, x.H, x.N, x.N), dtype=torch.bfloat16, device="cuda")
+    attnw.attnw_gemm_scores(Q, K, S, x.B, x.H, x.N, x.d, 1.0, attnw.ATTNW_BF16)
+    torch.cuda.synchronize()
+    Sv = S.view(x.B * x.H * x.N, x.N)
+    picks = []
+    for bh in (0, x.B * x.H // 2, x.B * x.H - 1):
+        picks += [bh * x.N + r for r in _sample_rows(x.N, seed=90 + bh, n_random=6)]
+    picks = sorted(set(picks))
+    before = Sv[picks].cpu().view(torch.int16).numpy().view(np.uint16)
+    attnw.attnw_scale(S, S, S.numel(), scale, attnw.ATTNW_BF16)
+    torch.cuda.synchronize()
+    after = Sv[picks].cpu().view(torch.int16).numpy().view(np.uint16)
+    exact = oracle.scale(before, "bf16", scale)
+    # one rounding to nearest even of the exact product (fp64 -> bf16, normal range)
+    u = exact.view(np.uint64)
+    r = ((u + ((u >> np.uint64(45)) & np.uint64(1)) + np.uint64((1 << 44) - 1)) >> np.uint64(45)) << np.uint64(45)
+    want = (r.view(np.float64).astype(np.float32).view(np.uint32) >> np.uint32(16)).astype(np.uint16)
+    assert np.array_equal(after, want), "scaling stage differs from the exact product rounded once"
+    Pm = gu.run_softmax(Sv, x.B * x.H * x.N, x.N, "bf16")
+    _row_sums_ok(Pm.view(x.B, x.H, x.N, x.N), gu.ROWSUM_BF16)
+    gu.check_weights(gu.to_f64(Pm[picks]), oracle.softmax(after, "bf16"), "bf16", f"{name} three-kernel softmax")
+
+
 def test_long_rows_have_no_systematic_error():
     """One rounding to bf16 hides errors of a few 1e-4 in a row's normaliser from the element-wise
     bound most of the time.  The mean signed relative error of a row does not: rounding errors of

@@ -217,3 +217,30 @@ def test_gemm_scores_round_kernel_negative_scale_matches_general_kernel(monkeypa
     monkeypatch.setenv("ATTNW_FUSED_KERNEL", "twopass")
     S2 = gu.run_scores(x, guard=4096)
     assert torch.equal(S.view(torch.int16), S2.view(torch.int16))
+
+
+# ---- softmax with separate storage types for scores and weights ------------------------------------
+
+@pytest.mark.parametrize("src,dst", [("f32", "bf16"), ("bf16", "f32")])
+@pytest.mark.parametrize("cols", [8, 24, 1000, 2048, 2049, 16384, 40000])
+def test_softmax_cast(src, dst, cols):
+    import paper_2407_13885_amd as attnw
+    rows = 37 if cols < 10000 else 5
+    s = wl.softmax_inputs("t", src, rows, cols, seed=1300 + cols, sigma=2.0)
+    S = gu.to_dev(s.S, src)
+    P, canary = gu.empty_like_out((rows, cols), dst, guard=4096)
+    attnw.attnw_softmax_cast(S, P, rows, cols, gu.DT[src], gu.DT[dst])
+    torch.cuda.synchronize()
+    assert gu.guards_intact(canary), "softmax wrote outside P"
+    gu.check_weights(gu.to_f64(P), oracle.softmax(s.S, src), dst, f"softmax {src}->{dst} cols={cols}")
+
+
+def test_softmax_cast_with_equal_types_is_attnw_softmax():
+    import paper_2407_13885_amd as attnw
+    s = wl.softmax_inputs("t", "bf16", 64, 2048, seed=7, sigma=2.0)
+    S = gu.to_dev(s.S, "bf16")
+    a = gu.run_softmax(S, 64, 2048, "bf16")
+    b = torch.empty_like(a)
+    attnw.attnw_softmax_cast(S, b, 64, 2048, attnw.ATTNW_BF16, attnw.ATTNW_BF16)
+    torch.cuda.synchronize()
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
