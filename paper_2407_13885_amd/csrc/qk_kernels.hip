@@ -170,7 +170,8 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
             const u32x4 v = *reinterpret_cast<const u32x4*>(stage + row * ST_PITCH + (lane % CPS) * 16);
             T* dst = out_lane + (int64_t)(it * RPI) * N + kseg0;
             if constexpr (FAST) {
-                *reinterpret_cast<u32x4*>(dst) = v;
+                // past the caches: the output is far larger than the K of a head, which then stays in L2
+                __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(dst));
             } else {
                 const int q = qw0 + row;
                 const int key0 = kseg0 + (lane % CPS) * EPC;
