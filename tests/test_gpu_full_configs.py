@@ -133,3 +133,31 @@ def test_long_rows_have_no_systematic_error():
         mean_rel = ((got - ref) / ref).mean(-1)
         worst = float(np.abs(mean_rel).max())
         assert worst <= 6e-5, f"head {h}: mean signed relative error of a row {worst:.2e} (row {rows[int(np.abs(mean_rel).argmax())]})"
+
+
+def test_fused_and_attention_at_the_longest_supported_row():
+    """N = 32768 is the longest sequence the round-based kernel takes (one head: P is 2 GiB); sampled rows
+    against the oracle, every row sum, and the attention output of the same inputs on sampled rows."""
+    import paper_2407_13885_amd as attnw
+    x = wl.fused_inputs("t", "bf16", 1, 1, 32768, 64, seed=32, row_factor=(0.5, 2.0))
+    P = gu.run_fused(x)
+    _row_sums_ok(P, gu.ROWSUM_BF16)
+    rows = _sample_rows(x.N, seed=33, n_random=16)
+    got = gu.to_f64(P[0, 0][rows])
+    ref = np.concatenate([oracle.attention_weights(x.Q[0, 0], x.K[0, 0], "bf16", x.scale, rows=(r, r + 1)) for r in rows])
+    gu.check_weights(got, ref, "bf16", "N = 32768 sampled rows")
+    del P
+    torch.cuda.empty_cache()
+    V = wl.value_inputs(x, seed=34)
+    Q, K, Vd = gu.to_dev(x.Q, "bf16"), gu.to_dev(x.K, "bf16"), gu.to_dev(V, "bf16")
+    O = torch.empty((1, 1, x.N, x.d), dtype=torch.bfloat16, device="cuda")
+    attnw.attnw_attention(Q, K, Vd, O, 1, 1, x.N, x.d, float(x.scale), attnw.ATTNW_BF16)
+    torch.cuda.synchronize()
+    Of = gu.to_f64(O)[0, 0]
+    Vw = np.abs(wl.widen(V[0, 0], "bf16"))
+    for r in rows[::3]:
+        ref_o, Pr = oracle.attention_output(x.Q[0, 0], x.K[0, 0], V[0, 0], "bf16", x.scale, rows=(r, r + 1),
+                                            return_weights=True)
+        A = Pr @ Vw
+        tol = 2.0 ** -8 * (A + np.abs(ref_o)) * 1.02 + 1e-6 * A
+        assert (np.abs(Of[r:r + 1] - ref_o) <= tol).all(), f"attention output row {r} at N = 32768"
