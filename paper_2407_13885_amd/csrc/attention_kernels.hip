@@ -73,7 +73,9 @@ struct AttnCfg {
     static constexpr int LDS_TOTAL = 2 * K_TILE_BYTES + 2 * VT_BYTES;
 };
 
-template <int DB, int QB>
+// TAIL: N is not a whole number of tiles / strips.  Rows past the end are read as row N-1 (every load
+// stays inside the arrays), their weights are forced to 0 and their queries are not stored.
+template <int DB, int QB, bool TAIL>
 __global__ __launch_bounds__(512)
 void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
                       uint16_t* __restrict__ O, int N, float c, uint32_t sign_flip, uint32_t strips, uint32_t total)
@@ -106,22 +108,23 @@ void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
     char* Oh = reinterpret_cast<char*>(O) + (int64_t)bh * N * DB;
     const int q0 = strip * BM + wave * QW;
 
+    auto row_in = [&](int r) __attribute__((always_inline)) { return TAIL ? min(r, N - 1) : r; };
+
     // ---- Q fragments (a negative scale negates Q) ----------------------------------------------------
     u32x4 qf[QB][G];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
         for (int g = 0; g < G; ++g)
-            qf[qb][g] = *reinterpret_cast<const u32x4*>(Qh + (int64_t)(q0 + qb * 32 + l32) * DB + (2 * g + half) * 16) ^ sign_flip;
+            qf[qb][g] = *reinterpret_cast<const u32x4*>(Qh + (int64_t)row_in(q0 + qb * 32 + l32) * DB + (2 * g + half) * 16) ^ sign_flip;
 
     // ---- per-lane constants ----------------------------------------------------------------------------
-    int goff[K_LOADS];
+    int k_key[K_LOADS], k_ch16[K_LOADS];     // K tile transfer j of this lane: key within the tile, byte offset in its row
 #pragma unroll
     for (int j = 0; j < K_LOADS; ++j) {
         const int s = (wave + NW * j) * 64 + lane;
-        const int key = s / CPR;
-        const int ch = (s % CPR) ^ ((key / C::RPL) & C::SWZ_MASK);
-        goff[j] = key * DB + ch * 16;
+        k_key[j] = s / CPR;
+        k_ch16[j] = ((s % CPR) ^ ((k_key[j] / C::RPL) & C::SWZ_MASK)) * 16;
     }
     const uint32_t k_lds_base = (uint32_t)(uintptr_t)(lds_ptr)(k_lds);
     int kfrag_off[G];
@@ -132,31 +135,32 @@ void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
     }
     // V tile: wave-wide load j covers 64 consecutive keys x one 16-byte chunk (8 output columns); the
     // 8 values go to 8 Vt rows at the key's permuted position (64 lanes -> 128 contiguous bytes per row)
-    int v_goff[V_LOADS], v_ldsoff[V_LOADS];
+    int v_key[V_LOADS], v_ch16[V_LOADS], v_ldsoff[V_LOADS];
 #pragma unroll
     for (int j = 0; j < V_LOADS; ++j) {
         const int idx = wave + NW * j;
         const int key = (idx & 1) * 64 + lane;
         const int ch = idx >> 1;
         const int pos = (key & ~12) | ((key & 4) << 1) | ((key & 8) >> 1);   // bits 2 and 3 swapped
-        v_goff[j] = key * DB + ch * 16;
+        v_key[j] = key;
+        v_ch16[j] = ch * 16;
         v_ldsoff[j] = ch * 8 * VT_PITCH + pos * 2;
     }
     // Vt fragment of (block dvb, sub-tile u, group m): row dvb*32 + l32, keys u*32 + 16m + 8*half ..
     const int vfrag_off = l32 * VT_PITCH + half * 16;
 
-    const int n_tiles = N / BN;
+    const int n_tiles = (N + BN - 1) / BN;
     auto k_issue = [&](int tile, int buf) __attribute__((always_inline)) {
-        const char* tile_base = Kh + (int64_t)tile * (BN * DB);
 #pragma unroll
         for (int i = 0; i < K_LOADS; ++i)
-            dma16_untracked_a(tile_base + goff[i], k_lds_base + buf * K_TILE_BYTES + (wave + NW * i) * 1024);
+            dma16_untracked_a(Kh + (int64_t)row_in(tile * BN + k_key[i]) * DB + k_ch16[i],
+                              k_lds_base + buf * K_TILE_BYTES + (wave + NW * i) * 1024);
     };
     u32x4 vreg[V_LOADS];
     auto v_load = [&](int tile) __attribute__((always_inline)) {
-        const char* tile_base = Vh + (int64_t)tile * (BN * DB);
 #pragma unroll
-        for (int j = 0; j < V_LOADS; ++j) vreg[j] = *reinterpret_cast<const u32x4*>(tile_base + v_goff[j]);
+        for (int j = 0; j < V_LOADS; ++j)
+            vreg[j] = *reinterpret_cast<const u32x4*>(Vh + (int64_t)row_in(tile * BN + v_key[j]) * DB + v_ch16[j]);
     };
     auto v_scatter = [&](int buf) __attribute__((always_inline)) {
         char* base = vt_lds + buf * VT_BYTES;
@@ -182,7 +186,7 @@ void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
     }
 
     // one 128-key tile out of buffers `buf`
-    auto compute_tile = [&](auto bufc) __attribute__((always_inline)) {
+    auto compute_tile = [&](auto bufc, int t) __attribute__((always_inline)) {
         constexpr int BUF = decltype(bufc)::value;
         const char* kb = k_lds + BUF * K_TILE_BYTES;
         const char* vb = vt_lds + BUF * VT_BYTES + vfrag_off;
@@ -232,6 +236,15 @@ void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
                 float p[16];
 #pragma unroll
                 for (int r = 0; r < 16; ++r) p[r] = fast_exp2(__builtin_fmaf(s[qb][r], c, -mb));
+                if constexpr (TAIL) {
+                    // keys past the end were read as key N-1 (their scores change no maximum): no weight
+                    if (t == n_tiles - 1) {
+                        const int kbase = t * BN + u * 32 + 4 * half;
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            if (kbase + 8 * (r / 4) + (r % 4) >= N) p[r] = 0.0f;
+                    }
+                }
                 float sum = p[0];
 #pragma unroll
                 for (int r = 1; r < 16; ++r) sum += p[r];
@@ -262,20 +275,25 @@ void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
         const int nxt = t + 1 < n_tiles ? t + 1 : 0;      // past the end: a valid tile, unused
         k_issue(nxt, BUF ^ 1);
         v_load(nxt);
-        compute_tile(bufc);
+        compute_tile(bufc, t);
         v_scatter(BUF ^ 1);
         wait_vmem();
         __syncthreads();
     };
-    for (int t = 0; t < n_tiles; t += 2) {
-        iteration(t, IC<0>{});
-        iteration(t + 1, IC<1>{});
+    if constexpr (TAIL) {
+        for_tiles(0, 0, n_tiles, iteration);
+    } else {
+        for (int t = 0; t < n_tiles; t += 2) {      // N is a multiple of two tiles
+            iteration(t, IC<0>{});
+            iteration(t + 1, IC<1>{});
+        }
     }
 
     // ---- normalise, round once, store: a lane owns runs of 4 consecutive output columns of its query -----------
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
         const float inv = 1.0f / half_sum(l_run[qb]);
+        if (TAIL && q0 + qb * 32 + l32 >= N) continue;
         char* orow = Oh + (int64_t)(q0 + qb * 32 + l32) * DB + half * 8;
 #pragma unroll
         for (int b = 0; b < DVB; ++b)
@@ -288,17 +306,17 @@ void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
     }
 }
 
-template <int DB, int QB>
+template <int DB, int QB, bool TAIL>
 hipError_t launch_attention_t(const void* Q, const void* K, const void* V, void* O, int64_t BH, int N, float scale,
                               hipStream_t stream)
 {
     using C = AttnCfg<DB, QB>;
-    const uint32_t strips = (uint32_t)(N / C::BM);
+    const uint32_t strips = (uint32_t)((N + C::BM - 1) / C::BM);
     const uint64_t total = (uint64_t)BH * strips;
     const uint32_t grid = (uint32_t)((total + 7) / 8 * 8);
     const float c = fabsf(scale) * kLog2e;
     const uint32_t flip = scale < 0.0f ? Mma<uint16_t>::kSignMask : 0u;
-    hipLaunchKernelGGL((attention_kernel<DB, QB>), dim3(grid), dim3(512), 0, stream, static_cast<const uint16_t*>(Q),
+    hipLaunchKernelGGL((attention_kernel<DB, QB, TAIL>), dim3(grid), dim3(512), 0, stream, static_cast<const uint16_t*>(Q),
                        static_cast<const uint16_t*>(K), static_cast<const uint16_t*>(V), static_cast<uint16_t*>(O), N, c,
                        flip, strips, (uint32_t)total);
     return hipGetLastError();
@@ -309,17 +327,21 @@ hipError_t launch_attention_t(const void* Q, const void* K, const void* V, void*
 bool attention_supported(int64_t BH, int64_t N, int64_t d)
 {
     if (d != 64 && d != 128) return false;
-    if (N < 256 || (N % 256) != 0 || N > ((int64_t)1 << 24)) return false;
-    return BH * (N / 256) <= (int64_t)0x7ffffff0;
+    if (N < 1 || N > ((int64_t)1 << 24)) return false;
+    return BH * ((N + 255) / 256) <= (int64_t)0x7ffffff0;
 }
 
 hipError_t launch_attention(const void* Q, const void* K, const void* V, void* O, int64_t BH, int64_t N, int64_t d,
                             float scale, hipStream_t stream)
 {
-    if (d == 128) return launch_attention_t<256, 1>(Q, K, V, O, BH, (int)N, scale, stream);
+    if ((N % 256) != 0) {   // any length: rows past the end are clamped and masked
+        if (d == 128) return launch_attention_t<256, 1, true>(Q, K, V, O, BH, (int)N, scale, stream);
+        return launch_attention_t<128, 1, true>(Q, K, V, O, BH, (int)N, scale, stream);
+    }
+    if (d == 128) return launch_attention_t<256, 1, false>(Q, K, V, O, BH, (int)N, scale, stream);
     // two query blocks per wave (512-query strips) when that still gives every compute unit a workgroup
-    if ((N % 512) == 0 && BH * (N / 512) >= 200) return launch_attention_t<128, 2>(Q, K, V, O, BH, (int)N, scale, stream);
-    return launch_attention_t<128, 1>(Q, K, V, O, BH, (int)N, scale, stream);
+    if ((N % 512) == 0 && BH * (N / 512) >= 200) return launch_attention_t<128, 2, false>(Q, K, V, O, BH, (int)N, scale, stream);
+    return launch_attention_t<128, 1, false>(Q, K, V, O, BH, (int)N, scale, stream);
 }
 
 }  // namespace attnw

@@ -65,6 +65,26 @@ def test_attention_bf16_small(B, H, N, d):
 
 
 @pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("N", [1, 2, 3, 31, 33, 100, 127, 128, 129, 255, 257, 320, 600, 1000])
+def test_attention_any_length(N, d):
+    """Lengths that are not whole tiles or strips: rows past the end are clamped on the way in, their
+    weights forced to zero, their queries not stored (the guard band around O stays untouched)."""
+    x = wl.fused_inputs("t", "bf16", 1, 2, N, d, seed=1500 + N + d, row_factor=(0.5, 2.0))
+    V = wl.value_inputs(x, seed=1501 + N)
+    O = gu.to_f64(_run(x, V))
+    for h in range(2):
+        _check_rows(O[0, h], x, V, 0, h, (0, N), f"attention N={N} d={d} head {h}")
+
+
+def test_attention_any_length_scale_zero_is_the_column_mean():
+    x = wl.fused_inputs("t", "bf16", 1, 1, 333, 64, seed=21, scale=0.0)
+    V = wl.value_inputs(x, seed=22)
+    O = gu.to_f64(_run(x, V))
+    mean = wl.widen(V[0, 0], "bf16").mean(axis=0)
+    assert np.abs(O[0, 0] - mean).max() <= 2.0 ** -8 * np.abs(wl.widen(V[0, 0], "bf16")).mean(axis=0).max()
+
+
+@pytest.mark.parametrize("d", [64, 128])
 def test_attention_negative_scale_sharp_rows_and_special_values(d):
     x = wl.fused_inputs("t", "bf16", 1, 2, 768, d, seed=41 + d, scale=-1.0 / math.sqrt(d), row_factor=(0.5, 3.0))
     V = wl.value_inputs(x, seed=42 + d)
