@@ -358,7 +358,8 @@ def main() -> int:
         "ms_per_step": head["ms_per_step"],
         "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",     # arithmetic type between load and store (bf16 operands on the matrix cores, fp32 accumulate)
+        # bf16 operands on the matrix cores and bf16 storage, fp32 accumulation and fp32 softmax arithmetic
+        "dtype": "bf16" if head["shape"].get("dtype", "bf16") == "bf16" else "f32",
         "data": "synthetic",
         "config": {"workload": f"{args.workload}: {head['call']} {json.dumps(head['shape'])}",
                    "generator": wl.GENERATOR_ID, "buffer_sets": head["buffer_sets"]},
