@@ -146,7 +146,8 @@ const char* attnw_status_string(int status)
     case ATTNW_ERR_NULL: return "null pointer";
     case ATTNW_ERR_SHAPE: return "bad shape (negative dimension or size overflow)";
     case ATTNW_ERR_DTYPE: return "unknown dtype";
-    case ATTNW_ERR_UNSUPPORTED: return "unsupported size (d must be a multiple of 16 in [16, 256]; grid limits)";
+    case ATTNW_ERR_UNSUPPORTED:
+        return "unsupported dtype / head size / extent for this entry point (limits are listed per call in attnw.h)";
     case ATTNW_ERR_ALIGN: return "pointer not 16-byte aligned";
     case ATTNW_ERR_ALIAS: return "output overlaps an input";
     case ATTNW_ERR_LAUNCH: return "kernel launch failed";

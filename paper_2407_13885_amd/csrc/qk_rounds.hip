@@ -28,6 +28,10 @@
 // As in the two-pass kernel, the MFMA computes the transposed tile (K sub-tile) * (Q block)^T: a
 // lane's 16 accumulators are 16 keys of one query.
 //
+// SCORES = true turns the same machinery into the score GEMM of the unfused pipelines: every round
+// is a weights-only round of its own strip with p = scale * s in place of the exponential, no
+// statistics and no handover (the staging and store path is what makes it worth sharing).
+//
 // K tiles travel global -> LDS directly (16 bytes per lane), double buffered.  The transfers are
 // issued from inline assembly so that the only waits on them are the explicit vmcnt waits below:
 // vector-memory operations retire in order, hence "at most n outstanding" with n = the number of
