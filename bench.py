@@ -238,7 +238,7 @@ def wl_value_inputs(x):
     return wl.value_inputs(x, seed=12345)
 
 
-def cpu_baseline_fused(x, rows_per_head=1024):
+def cpu_baseline_fused(x, rows_per_head=4096):
     """The oracle as it stands, on the host cores, on a bounded sample of the workload."""
     import oracle
     rows_per_head = min(rows_per_head, x.N)
