@@ -8,7 +8,7 @@
 
 namespace {
 
-constexpr int kVersion = 100;   // 0.1.0
+constexpr int kVersion = 104;   // 0.1.4: major * 10000 + minor * 100 + patch; a patch step per entry point added since 0.1.0
 
 bool mul_overflows(int64_t a, int64_t b, int64_t* out)
 {

@@ -153,6 +153,30 @@ def test_binding_raises_with_status(lib):
     assert ei.value.status == E_ALIGN and "aligned" in str(ei.value)
 
 
+def test_header_is_plain_c_and_a_c_program_links(lib, tmp_path):
+    """include/attnw.h compiled as C99 with warnings as errors; a C caller links against libattnw.so and gets
+    the validation answers without any GPU (validation runs before the first HIP call)."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler on this host")
+    src = tmp_path / "caller.c"
+    src.write_text(
+        '#include "attnw.h"\n#include <stdio.h>\n'
+        "int main(void) {\n"
+        "  int bad = attnw_softmax((void *)16, (void *)32, -1, 4, ATTNW_BF16, 0);\n"
+        "  int empty = attnw_fused(0, 0, 0, 0, 1, 128, 64, 0.125f, ATTNW_F32, 0);\n"
+        '  printf("%d %d %d %s\\n", bad, empty, attnw_version(), attnw_status_string(bad));\n'
+        "  return 0;\n}\n")
+    exe = tmp_path / "caller"
+    libdir = os.path.dirname(binding.library_path())
+    subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe), "-L", libdir, "-l:libattnw.so", f"-Wl,-rpath,{libdir}"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split(None, 3)
+    assert int(out[0]) == E_SHAPE and int(out[1]) == OK and int(out[2]) >= 100 and "shape" in out[3]
+
+
 def test_product_package_does_not_import_the_oracle():
     """The oracle is test infrastructure: nothing under the product package may use it."""
     pkg = os.path.join(ROOT, "paper_2407_13885_amd")
