@@ -244,3 +244,43 @@ def test_softmax_cast_with_equal_types_is_attnw_softmax():
     attnw.attnw_softmax_cast(S, b, 64, 2048, attnw.ATTNW_BF16, attnw.ATTNW_BF16)
     torch.cuda.synchronize()
     assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+# ---- concurrent callers ---------------------------------------------------------------------------
+
+def test_calls_from_two_host_threads_on_two_streams():
+    """The library keeps no mutable state between calls: two host threads, each on a stream of its own,
+    get the bits a single caller gets."""
+    import threading
+    import paper_2407_13885_amd as attnw
+    xs = [wl.fused_inputs("t", "bf16", 1, 4, 1024, 64, seed=50 + i) for i in range(2)]
+    want = [gu.run_fused(x).view(torch.int16).clone() for x in xs]
+    dev = [(gu.to_dev(x.Q, "bf16"), gu.to_dev(x.K, "bf16")) for x in xs]
+    outs = [torch.empty((1, 4, 1024, 1024), dtype=torch.bfloat16, device="cuda") for _ in xs]
+    streams = [torch.cuda.Stream() for _ in xs]
+    torch.cuda.synchronize()
+    errors = []
+
+    def worker(i):
+        try:
+            x = xs[i]
+            for _ in range(20):
+                attnw.attnw_fused(dev[i][0], dev[i][1], outs[i], x.B, x.H, x.N, x.d, float(x.scale), attnw.ATTNW_BF16,
+                                  streams[i])
+                attnw.attnw_softmax(outs[i].view(-1, x.N), outs[i].view(-1, x.N), x.H * x.N, x.N, attnw.ATTNW_BF16,
+                                    streams[i])
+                attnw.attnw_fused(dev[i][0], dev[i][1], outs[i], x.B, x.H, x.N, x.d, float(x.scale), attnw.ATTNW_BF16,
+                                  streams[i])
+            streams[i].synchronize()
+        except Exception as e:      # surfaced in the main thread
+            errors.append(e)
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for i in range(2):
+        assert torch.equal(outs[i].view(torch.int16), want[i]), f"thread {i}"
