@@ -129,3 +129,41 @@ def test_three_kernel_pipeline_stage_by_stage(dtype, N, d):
         ref_p = oracle.attention_weights_bh(x.Q, x.K, dtype, scale)
         gu.check_weights(gu.to_f64(P).reshape(1, H, N, N), ref_p, dtype, "three-kernel end to end fp32",
                          abs_f32=2e-6)
+
+
+def test_three_kernel_pipeline_in_a_captured_graph():
+    """The entry points only launch kernels on the caller's stream (no allocation, no memset, no
+    synchronisation), so a stream capture records them; every replay must give the eager bits, also
+    with eager work and synchronisations between the replays."""
+    N, d, H = 512, 64, 3
+    scale = float(np.float32(1.0 / math.sqrt(d)))
+    x = wl.fused_inputs("t", "bf16", 1, H, N, d, seed=2100, scale=1.0)
+    Q, K = gu.to_dev(x.Q, "bf16"), gu.to_dev(x.K, "bf16")
+    S = torch.empty((1, H, N, N), dtype=torch.bfloat16, device="cuda")
+    P = torch.empty_like(S)
+
+    def pipeline(stream):
+        attnw.attnw_gemm_scores(Q, K, S, 1, H, N, d, 1.0, attnw.ATTNW_BF16, stream)
+        attnw.attnw_scale(S, S, S.numel(), scale, attnw.ATTNW_BF16, stream)
+        attnw.attnw_softmax(S.view(H * N, N), P.view(H * N, N), H * N, N, attnw.ATTNW_BF16, stream)
+
+    pipeline(torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    want = P.view(torch.int16).clone()
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        pipeline(side)                                    # warm-up on the capture stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            pipeline(torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    for rep in range(4):
+        P.fill_(-3.0)                                     # eager work between the replays
+        S.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(P.view(torch.int16), want), f"replay {rep}"
