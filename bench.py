@@ -349,7 +349,7 @@ def main() -> int:
         print("[bench] cpu_baseline (oracle on host cores) ...", file=sys.stderr, flush=True)
         cpu = cpu_baseline_softmax(x) if args.workload == "c2" else cpu_baseline_fused(x)
 
-    dominant = "softmax_rows_kernel" if args.workload == "c2" else "qk_rounds_kernel"
+    dominant = {"c2": "softmax_rows_kernel", "c3": "qk_resident_kernel"}.get(args.workload, "qk_rounds_kernel")
     line = {
         "metric": METRIC,
         "value": head["elements_per_s"],

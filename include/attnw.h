@@ -33,12 +33,15 @@
  *   - The library keeps no mutable global state apart from a per-device cache
  *     of the compute-unit count; calls from several host threads on different
  *     streams are safe.
- *   - Environment: ATTNW_FUSED_KERNEL=twopass makes attnw_fused and
- *     attnw_gemm_scores use the general two-pass kernel also for the bf16
- *     shapes that otherwise take the round-based kernel (N a multiple of 256;
- *     d = 64 or 128 for attnw_fused, d = 64 for attnw_gemm_scores); fused
- *     results of the two agree to rounding of the row sum, scores bit for
- *     bit.  Read at every call.
+ *   - Environment: ATTNW_FUSED_KERNEL selects among the kernels behind
+ *     attnw_fused / attnw_gemm_scores for bf16 shapes that several of them
+ *     serve (read at every call; tests and measurements compare them):
+ *       unset    d = 64 and N = 512 or 1024: scores of a strip held in
+ *                registers, one sweep; else N a multiple of 256 and d = 64 or
+ *                128 (scores: d = 64): round-based kernel; else general kernel
+ *       rounds   never the register-resident kernel
+ *       twopass  always the general two-pass kernel
+ *     Weights of the three agree to rounding of the row sum, scores bit for bit.
  */
 #ifndef ATTNW_H
 #define ATTNW_H

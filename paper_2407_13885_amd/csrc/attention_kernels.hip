@@ -26,13 +26,6 @@
 namespace attnw {
 namespace {
 
-__device__ __forceinline__ void dma16_untracked_a(const char* src, uint32_t lds_base)
-{
-#if defined(__HIP_DEVICE_COMPILE__)
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(src) : "memory");
-#endif
-}
-
 // value of the other half-wave's lane (l ^ 32) combined with the own one
 __device__ __forceinline__ float half_max(float x)
 {
@@ -126,7 +119,7 @@ void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
         k_key[j] = s / CPR;
         k_ch16[j] = ((s % CPR) ^ ((k_key[j] / C::RPL) & C::SWZ_MASK)) * 16;
     }
-    const uint32_t k_lds_base = (uint32_t)(uintptr_t)(lds_ptr)(k_lds);
+    const uint32_t k_lds_base = lds_offset_of(k_lds);
     int kfrag_off[G];
     {
         const int swz = (l32 / C::RPL) & C::SWZ_MASK;
@@ -153,7 +146,7 @@ void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
     auto k_issue = [&](int tile, int buf) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < K_LOADS; ++i)
-            dma16_untracked_a(Kh + (int64_t)row_in(tile * BN + k_key[i]) * DB + k_ch16[i],
+            dma16_untracked(Kh + (int64_t)row_in(tile * BN + k_key[i]) * DB + k_ch16[i],
                               k_lds_base + buf * K_TILE_BYTES + (wave + NW * i) * 1024);
     };
     u32x4 vreg[V_LOADS];

@@ -15,6 +15,9 @@ hipError_t launch_softmax(DType in, DType out, const void* S, void* P, int64_t r
 hipError_t launch_qk(DType dt, bool scores_only, const void* Q, const void* K, void* out,
                      int64_t BH, int64_t N, int64_t d, float scale, hipStream_t stream);
 
+// Compute units of the current device (256 if the query fails).
+int compute_units();
+
 // bf16, by the round-based kernel: fused attention weights (statistics of one strip gathered while the
 // weights of the previous one are written) or, with scores_only, the scaled scores (one sweep per
 // strip through the same staging and store path; d = 64 only).  Only for the shapes
@@ -22,6 +25,12 @@ hipError_t launch_qk(DType dt, bool scores_only, const void* Q, const void* K, v
 bool qk_rounds_supported(int64_t BH, int64_t N, int64_t d);
 hipError_t launch_qk_rounds(bool scores_only, const void* Q, const void* K, void* out, int64_t BH, int64_t N, int64_t d,
                             float scale, hipStream_t stream);
+
+// Fused attention weights, bf16, d = 64, N = 512 or 1024: the scores of a 32-query strip stay in registers
+// between the contraction and the normalisation (one sweep over the keys).
+bool qk_resident_supported(int64_t BH, int64_t N, int64_t d);
+hipError_t launch_qk_resident(const void* Q, const void* K, void* out, int64_t BH, int64_t N, float scale,
+                              hipStream_t stream);
 
 // Y = scale * X over count elements, rounded once to the storage type; X == Y allowed.
 hipError_t launch_scale(DType dt, const void* X, void* Y, int64_t count, float scale, hipStream_t stream);

@@ -53,6 +53,21 @@ __device__ __forceinline__ void dma16(const char* __restrict__ src, char* __rest
     __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)dst, 16, 0, 0);
 }
 
+// The same transfer issued from inline assembly, which the compiler's wait-count pass does not see: the
+// only waits on it are the explicit vmcnt waits of the caller (vector-memory operations retire in order).
+// lds_base = byte offset in LDS, wave-uniform, below 64 KiB (it travels in M0).
+__device__ __forceinline__ void dma16_untracked(const char* src, uint32_t lds_base)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(src) : "memory");
+#endif
+}
+
+__device__ __forceinline__ uint32_t lds_offset_of(const void* p)
+{
+    return (uint32_t)(uintptr_t)(lds_ptr)(p);
+}
+
 template <int I> struct IC { static constexpr int value = I; };
 
 // f(IC<0>{}), f(IC<1>{}), ... f(IC<N-1>{})

@@ -415,11 +415,16 @@ hipError_t launch_qk(DType dt, bool scores_only, const void* Q, const void* K, v
                      int64_t BH, int64_t N, int64_t d, float scale, hipStream_t stream)
 {
     if (dt == DType::F32) return launch_qk_t<float>(scores_only, Q, K, out, BH, (int)N, (int)d, scale, stream);
-    // ATTNW_FUSED_KERNEL=twopass keeps bf16 problems on the two-pass kernel above (tests compare the two)
-    // (scores with 256-byte rows stay here: two co-resident workgroups of this kernel stream them faster)
-    if (qk_rounds_supported(BH, N, d) && (!scores_only || d == 64)) {
-        const char* force = getenv("ATTNW_FUSED_KERNEL");
-        if (!(force && strcmp(force, "twopass") == 0))
+    // ATTNW_FUSED_KERNEL=twopass keeps bf16 problems on the two-pass kernel above, =rounds keeps short sequences
+    // off the resident kernel (tests and measurements compare the three)
+    const char* force = getenv("ATTNW_FUSED_KERNEL");
+    const bool twopass = force && strcmp(force, "twopass") == 0;
+    const bool rounds = force && strcmp(force, "rounds") == 0;
+    if (!twopass) {
+        if (!scores_only && !rounds && qk_resident_supported(BH, N, d))
+            return launch_qk_resident(Q, K, out, BH, N, scale, stream);
+        // (scores with 256-byte rows stay on the general kernel: two co-resident workgroups of it stream them faster)
+        if (qk_rounds_supported(BH, N, d) && (!scores_only || d == 64))
             return launch_qk_rounds(scores_only, Q, K, out, BH, N, d, scale, stream);
     }
     return launch_qk_t<uint16_t>(scores_only, Q, K, out, BH, (int)N, (int)d, scale, stream);

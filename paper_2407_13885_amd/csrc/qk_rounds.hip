@@ -42,19 +42,6 @@
 namespace attnw {
 namespace {
 
-// 16 bytes per lane, global -> LDS (lane i lands at lds_base + 16 i; lds_base is wave-uniform).
-__device__ __forceinline__ void dma16_untracked(const char* src, uint32_t lds_base)
-{
-#if defined(__HIP_DEVICE_COMPILE__)
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(src) : "memory");
-#endif
-}
-
-__device__ __forceinline__ uint32_t lds_offset_of(const void* p)
-{
-    return (uint32_t)(uintptr_t)(lds_ptr)(p);
-}
-
 template <int DB, int WQ, int WK>
 struct RoundsCfg {
     static constexpr int SUBS = 2;                // 32-key sub-tiles per wave per K tile
@@ -396,20 +383,6 @@ void qk_rounds_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
     wait_vmem();   // no K transfer may be in flight when the workgroup's LDS is released
 }
 
-// compute units of the current device (workgroups are persistent: one per compute unit)
-int compute_units()
-{
-    static int cached[64] = {};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-    int n = __atomic_load_n(&cached[dev], __ATOMIC_RELAXED);
-    if (n == 0) {
-        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-        __atomic_store_n(&cached[dev], n, __ATOMIC_RELAXED);
-    }
-    return n;
-}
-
 template <int DB, int WQ, int WK, bool SCORES>
 hipError_t launch_rounds(const void* Q, const void* K, void* out, int64_t BH, int N, float scale, hipStream_t stream)
 {
@@ -428,6 +401,20 @@ hipError_t launch_rounds(const void* Q, const void* K, void* out, int64_t BH, in
 }
 
 }  // namespace
+
+// compute units of the current device (persistent workgroups are sized by it); cached per device
+int compute_units()
+{
+    static int cached[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    int n = __atomic_load_n(&cached[dev], __ATOMIC_RELAXED);
+    if (n == 0) {
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        __atomic_store_n(&cached[dev], n, __ATOMIC_RELAXED);
+    }
+    return n;
+}
 
 bool qk_rounds_supported(int64_t BH, int64_t N, int64_t d)
 {

@@ -74,6 +74,27 @@ def test_fused_bf16_round_kernel_shapes(B, H, N, d):
     gu.check_weights(gu.to_f64(P), _oracle_heads(x), "bf16", f"round kernel {B}x{H}x{N}x{d}")
 
 
+# ---- fused bf16, d = 64, N = 512 or 1024: the kernel that keeps the scores of a strip in registers ---
+
+@pytest.mark.parametrize("B,H,N", [(1, 1, 512), (1, 3, 1024), (2, 5, 512), (1, 37, 1024)])
+def test_fused_bf16_resident_kernel(B, H, N):
+    x = wl.fused_inputs("t", "bf16", B, H, N, 64, seed=900 + H + N, row_factor=(0.5, 2.5))
+    P = gu.run_fused(x, guard=8192)
+    gu.check_weights(gu.to_f64(P), _oracle_heads(x), "bf16", f"resident kernel {B}x{H}x{N}x64")
+
+
+@pytest.mark.parametrize("N", [512, 1024])
+def test_fused_bf16_resident_kernel_negative_scale_and_other_kernels(N, monkeypatch):
+    x = wl.fused_inputs("t", "bf16", 1, 2, N, 64, seed=17 + N, scale=-0.2, row_factor=(0.5, 3.0))
+    ref = _oracle_heads(x)
+    P = gu.run_fused(x, guard=4096)
+    gu.check_weights(gu.to_f64(P), ref, "bf16", f"resident kernel, negative scale, N={N}")
+    # the same problem through the round-based and the two-pass kernel
+    for which in ("rounds", "twopass"):
+        monkeypatch.setenv("ATTNW_FUSED_KERNEL", which)
+        gu.check_weights(gu.to_f64(gu.run_fused(x, guard=4096)), ref, "bf16", f"{which} kernel, negative scale, N={N}")
+
+
 @pytest.mark.parametrize("d", [64, 128])
 def test_fused_bf16_round_kernel_negative_scale_and_sharp_rows(d):
     x = wl.fused_inputs("t", "bf16", 1, 3, 512, d, seed=31 + d, scale=-1.0 / math.sqrt(d), row_factor=(0.5, 3.0))
