@@ -19,8 +19,10 @@
 //   global    the eight waves exchange maxima, then sums, through LDS (two barriers per strip);
 //   weights   p = e / l, rounded once to bf16, staged per wave as [16 queries][64 keys], re-read
 //             16 bytes per lane and stored past the caches (8 rows x 128 bytes per instruction).
-// The Q rows of a strip are requested two strips ahead: vector-memory operations retire in order,
-// and a load behind a burst of stores would wait for it.
+// The Q rows of the next strip are requested before the stores of the current one are issued:
+// vector-memory operations retire in order, and a load behind a burst of stores would wait for it.
+// While the exponentials of a strip are taken, the scores of the next strip of the same head are
+// accumulated into a second register set, one MFMA per chunk of vector work.
 #include "launchers.h"
 #include "qk_common.h"
 
@@ -132,18 +134,128 @@ void qk_resident_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restri
 
     uint32_t parity = 0;
     uint32_t head_in_lds = 0xffffffffu;
-    // Q fragments of this strip and of the next two.  Vector-memory operations retire in order, so waiting
-    // for the Q rows requested two strips ago leaves the stores of the last two strips in flight; with a
-    // distance of one the wave would stall on its own stores.
-    u32x4 qf[G], qf1[G], qf2[G];
-    if (s_cur < s_end) {
-        load_q(qf, s_cur);
-        load_q(qf1, s_cur + 1 < s_end ? s_cur + 1 : s_cur);
-    }
-    for (uint32_t strip_id = s_cur; strip_id < s_end; ++strip_id) {
+    // Q fragments of this strip and of the next one (requested before this strip's stores are issued:
+    // vector-memory operations retire in order, and a load behind a burst of stores would wait for it)
+    u32x4 qf[G], qf1[G];
+    if (s_cur < s_end) load_q(qf, s_cur);
+    // Two accumulator sets: while the exponentials of one strip are taken (vector ALU), the scores of the
+    // next strip of the same head are accumulated into the other set (matrix cores), one MFMA per chunk of
+    // vector work from the same instruction stream.
+    f32x16 acc_a[NT], acc_b[NT];
+    constexpr int NMMA = NT * G;                  // MFMAs of one sweep
+    // fragment of MFMA i of a sweep: piece i / G, group i % G
+    auto k_frag = [&](auto ic) __attribute__((always_inline)) -> u32x4 {
+        constexpr int i = decltype(ic)::value;
+        return *reinterpret_cast<const u32x4*>(k_lds + (i / G) * PIECE_BYTES + frag_off[i % G]);
+    };
+    auto mma_step = [&](f32x16 (&A)[NT], const u32x4 (&q)[G], const u32x4& kf, auto ic) __attribute__((always_inline)) {
+        constexpr int i = decltype(ic)::value;
+        if constexpr (i % G == 0) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) A[i / G][r] = 0.0f;
+        }
+        Mma<uint16_t>::run(A[i / G], kf, q[i % G]);
+    };
+    // a sweep on its own (first strip of a list or of a head)
+    auto sweep = [&](f32x16 (&A)[NT], const u32x4 (&q)[G]) __attribute__((always_inline)) {
+        static_for<NMMA>([&](auto ic) __attribute__((always_inline)) { mma_step(A, q, k_frag(ic), ic); });
+    };
+
+    // one strip whose scores are in X; if `ahead`, the scores of the next strip (Q fragments qn) go to Y
+    auto strip_body = [&](f32x16 (&X)[NT], f32x16 (&Y)[NT], const u32x4 (&qn)[G], bool ahead, char* out_rows)
+                          __attribute__((always_inline)) {
+        // ---- local maximum, exchanged for the global one ------------------------------------------------
+        float* const stat_m = stat + parity * (2 * NW * 32);
+        float* const stat_l = stat_m + NW * 32;
+        float m = kNegBig;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+#pragma unroll
+            for (int r = 0; r < 16; r += 2) m = max3(m, X[t][r], X[t][r + 1]);
+        }
+        m = fmaxf(m, __shfl_xor(m, 32, 64));      // lanes l and l + 32 hold the two halves of a query's keys
+        if (half == 0) stat_m[wave * 32 + l32] = m;
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < NW; ++w) m = fmaxf(m, stat_m[w * 32 + l32]);
+
+        // ---- exponentials in place of the scores and their local sum; the next strip's sweep rides along ----
+        const float mb = m * c;
+        float l = 0.0f;
+        constexpr int EPC = 16 * NT / NMMA;       // scores per chunk: one MFMA each
+        if (ahead) {
+            constexpr int LEAD = 3;               // fragments are fetched this many chunks ahead
+            u32x4 ring[LEAD];
+            static_for<LEAD>([&](auto ic) __attribute__((always_inline)) { ring[decltype(ic)::value] = k_frag(ic); });
+            static_for<NMMA>([&](auto ic) __attribute__((always_inline)) {
+                constexpr int i = decltype(ic)::value;
+#pragma unroll
+                for (int e = 0; e < EPC; ++e) {
+                    const int idx = i * EPC + e;
+                    const float x = fast_exp2(__builtin_fmaf(X[idx / 16][idx % 16], c, -mb));
+                    X[idx / 16][idx % 16] = x;
+                    l += x;
+                }
+                mma_step(Y, qn, ring[i % LEAD], ic);
+                if constexpr (i + LEAD < NMMA) ring[i % LEAD] = k_frag(IC<i + LEAD>{});
+                __builtin_amdgcn_sched_barrier(0);   // the chunk order is the schedule
+            });
+        } else {
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    X[t][r] = fast_exp2(__builtin_fmaf(X[t][r], c, -mb));
+                    l += X[t][r];
+                }
+            }
+        }
+        l += __shfl_xor(l, 32, 64);
+        if (half == 0) stat_l[wave * 32 + l32] = l;
+        __syncthreads();
+        l = 0.0f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) l += stat_l[w * 32 + l32];       // same order in every wave
+        const float inv = __builtin_amdgcn_rcpf(l);
+        // The exchange buffers alternate between strips: a wave that is already two barriers ahead writes the
+        // other pair, and cannot get further ahead than that.
+        parity ^= 1u;
+
+        // ---- weights: scale, round once, stage [ST_ROWS queries][64 keys], store -----------------------
+        char* const out_lane = out_rows + ((int64_t)(lane / CPS) * N + wave * 32 * NT + (lane % CPS) * 8) * 2;
+        static_for<NT / 2>([&](auto pc) __attribute__((always_inline)) {
+            constexpr int tp = decltype(pc)::value;
+#pragma unroll
+            for (int hb = 0; hb < ST_BLOCKS; ++hb) {   // queries ST_ROWS hb .. + ST_ROWS of the strip
+                if (l32 / ST_ROWS == hb) {
+#pragma unroll
+                    for (int u = 0; u < 2; ++u)
+#pragma unroll
+                        for (int r4 = 0; r4 < 4; ++r4) {
+                            const f32x16& a = X[2 * tp + u];
+                            u32x2 w = {pack_bf16x2(a[4 * r4] * inv, a[4 * r4 + 1] * inv),
+                                       pack_bf16x2(a[4 * r4 + 2] * inv, a[4 * r4 + 3] * inv)};
+                            *reinterpret_cast<u32x2*>(st_wr + (u * 32 + 8 * r4) * 2) = w;
+                        }
+                }
+                wave_sync_lds();                  // some of the lanes wrote, all of them read
+                u32x4 v[NF];
+#pragma unroll
+                for (int f = 0; f < NF; ++f) v[f] = *reinterpret_cast<const u32x4*>(st_rd + f * RPI * ST_PITCH);
+                wave_sync_lds();                  // the rows are in registers before the next block overwrites them
+#pragma unroll
+                for (int f = 0; f < NF; ++f)
+                    __builtin_nontemporal_store(
+                        v[f], reinterpret_cast<u32x4*>(out_lane + ((int64_t)(hb * ST_ROWS + f * RPI) * N + 64 * tp) * 2));
+            }
+        });
+    };
+
+    bool swept = false;                           // the current strip's scores are already in its accumulator set
+    auto one_strip = [&](f32x16 (&X)[NT], f32x16 (&Y)[NT], uint32_t strip_id) __attribute__((always_inline)) {
         const uint32_t bh = strip_id / strips_per_head;
         const uint32_t strip = strip_id - bh * strips_per_head;
-        char* const out_h = reinterpret_cast<char*>(out) + (int64_t)bh * N * (int64_t)N * 2;
+        char* const out_rows = reinterpret_cast<char*>(out) + ((int64_t)bh * N + strip * 32) * (int64_t)N * 2;
         if (bh != head_in_lds) {
             // ======== a new head: its K replaces the previous one ========================================
             k_request(bh);
@@ -152,93 +264,19 @@ void qk_resident_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restri
             __syncthreads();                      // K is in place
             head_in_lds = bh;
         }
-        {
-            load_q(qf2, strip_id + 2 < s_end ? strip_id + 2 : strip_id);
-
-            // ---- sweep: scores of the strip, resident in acc[0 .. NT) ---------------------------------
-            f32x16 acc[NT];
-            static_for<NT>([&](auto tc) __attribute__((always_inline)) {
-                constexpr int t = decltype(tc)::value;
-                u32x4 kf[G];
+        load_q(qf1, strip_id + 1 < s_end ? strip_id + 1 : strip_id);
+        const bool ahead = strip_id + 1 < s_end && (strip_id + 1) / strips_per_head == bh;
+        if (!swept) sweep(X, qf);
+        strip_body(X, Y, qf1, ahead, out_rows);
+        swept = ahead;
 #pragma unroll
-                for (int g = 0; g < G; ++g) kf[g] = *reinterpret_cast<const u32x4*>(k_lds + t * PIECE_BYTES + frag_off[g]);
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
-#pragma unroll
-                for (int g = 0; g < G; ++g) Mma<uint16_t>::run(acc[t], kf[g], qf[g]);
-            });
-
-            // ---- local maximum, exchanged for the global one --------------------------------------------
-            float* const stat_m = stat + parity * (2 * NW * 32);
-            float* const stat_l = stat_m + NW * 32;
-            float m = kNegBig;
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-#pragma unroll
-                for (int r = 0; r < 16; r += 2) m = max3(m, acc[t][r], acc[t][r + 1]);
-            }
-            m = fmaxf(m, __shfl_xor(m, 32, 64));  // lanes l and l + 32 hold the two halves of a query's keys
-            if (half == 0) stat_m[wave * 32 + l32] = m;
-            __syncthreads();
-#pragma unroll
-            for (int w = 0; w < NW; ++w) m = fmaxf(m, stat_m[w * 32 + l32]);
-
-            // ---- exponentials in place of the scores, local sum, exchanged for the global one -----------
-            const float mb = m * c;
-            float l = 0.0f;
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    acc[t][r] = fast_exp2(__builtin_fmaf(acc[t][r], c, -mb));
-                    l += acc[t][r];
-                }
-            }
-            l += __shfl_xor(l, 32, 64);
-            if (half == 0) stat_l[wave * 32 + l32] = l;
-            __syncthreads();
-            l = 0.0f;
-#pragma unroll
-            for (int w = 0; w < NW; ++w) l += stat_l[w * 32 + l32];   // same order in every wave
-            const float inv = __builtin_amdgcn_rcpf(l);
-            // The exchange buffers alternate between strips: a wave that is already two barriers ahead writes
-            // the other pair, and cannot get further ahead than that.
-            parity ^= 1u;
-
-            // ---- weights: scale, round once, stage [16 queries][64 keys], store -------------------------
-            char* const out_lane = out_h + ((int64_t)(strip * 32 + lane / CPS) * N + wave * 32 * NT + (lane % CPS) * 8) * 2;
-            static_for<NT / 2>([&](auto pc) __attribute__((always_inline)) {
-                constexpr int tp = decltype(pc)::value;
-#pragma unroll
-                for (int hb = 0; hb < ST_BLOCKS; ++hb) {   // queries ST_ROWS hb .. + ST_ROWS of the strip
-                    if (l32 / ST_ROWS == hb) {
-#pragma unroll
-                        for (int u = 0; u < 2; ++u)
-#pragma unroll
-                            for (int r4 = 0; r4 < 4; ++r4) {
-                                const f32x16& a = acc[2 * tp + u];
-                                u32x2 w = {pack_bf16x2(a[4 * r4] * inv, a[4 * r4 + 1] * inv),
-                                           pack_bf16x2(a[4 * r4 + 2] * inv, a[4 * r4 + 3] * inv)};
-                                *reinterpret_cast<u32x2*>(st_wr + (u * 32 + 8 * r4) * 2) = w;
-                            }
-                    }
-                    wave_sync_lds();              // some of the lanes wrote, all of them read
-                    u32x4 v[NF];
-#pragma unroll
-                    for (int f = 0; f < NF; ++f) v[f] = *reinterpret_cast<const u32x4*>(st_rd + f * RPI * ST_PITCH);
-                    wave_sync_lds();              // the rows are in registers before the next block overwrites them
-#pragma unroll
-                    for (int f = 0; f < NF; ++f)
-                        __builtin_nontemporal_store(
-                            v[f], reinterpret_cast<u32x4*>(out_lane + ((int64_t)(hb * ST_ROWS + f * RPI) * N + 64 * tp) * 2));
-                }
-            });
-#pragma unroll
-            for (int g = 0; g < G; ++g) {
-                qf[g] = qf1[g];
-                qf1[g] = qf2[g];
-            }
-        }
+        for (int g = 0; g < G; ++g) qf[g] = qf1[g];
+    };
+    // the two accumulator sets swap roles from strip to strip: the loop is unrolled by two so that each role
+    // is a fixed set of registers
+    for (uint32_t strip_id = s_cur; strip_id < s_end; strip_id += 2) {
+        one_strip(acc_a, acc_b, strip_id);
+        if (strip_id + 1 < s_end) one_strip(acc_b, acc_a, strip_id + 1);
     }
 }
 
