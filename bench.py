@@ -307,7 +307,7 @@ def main() -> int:
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (heads and query rows shard with no exchange; "
-              "see DESIGN.md); run it with --gpus 1", file=sys.stderr)
+              "every GPU would write its own slab of P); run it with --gpus 1", file=sys.stderr)
         return 2
 
     import torch
