@@ -365,7 +365,10 @@ def main() -> int:
                    "generator": wl.GENERATOR_ID, "buffer_sets": head["buffer_sets"]},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": head["hbm_GBps"], "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": head["hbm_frac_of_peak"],
-                     "traffic": measured_traffic(args.workload, head["call"])},
+                     "traffic": measured_traffic(args.workload, head["call"]),
+                     # what is observed to bind on this board (power and clock readings under profiles/)
+                     "observed_limit": ("board power cap (1400 W): shader clock throttled to 1.7-1.9 GHz"
+                                        if args.workload in ("c4", "c5") else None)},
         "cpu_baseline": cpu,
         "fused_vs_unfused_speedup": {k: v.get("fused_vs_unfused_speedup") for k, v in results.items()
                                      if "fused_vs_unfused_speedup" in v},
