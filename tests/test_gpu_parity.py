@@ -74,21 +74,32 @@ def test_fused_bf16_round_kernel_shapes(B, H, N, d):
     gu.check_weights(gu.to_f64(P), _oracle_heads(x), "bf16", f"round kernel {B}x{H}x{N}x{d}")
 
 
-# ---- fused bf16, d = 64, N = 512 or 1024: the kernel that keeps the scores of a strip in registers ---
+# ---- fused bf16, d = 64, N = 512 or 1024: the kernel that keeps the scores of a strip in registers.
+#      Many heads: strip lists that cross heads (K replaced in LDS); one head: short lists.  (d = 128, N = 512 would
+#      fit as well but measured slower than the round-based kernel, 49.6 against 42.4 us for 192 heads: it is not
+#      routed there; the shapes stay in the list as a test of that routing.)
 
-@pytest.mark.parametrize("B,H,N", [(1, 1, 512), (1, 3, 1024), (2, 5, 512), (1, 37, 1024)])
-def test_fused_bf16_resident_kernel(B, H, N):
-    x = wl.fused_inputs("t", "bf16", B, H, N, 64, seed=900 + H + N, row_factor=(0.5, 2.5))
+@pytest.mark.parametrize("B,H,N,d", [(1, 1, 512, 64), (1, 3, 1024, 64), (2, 5, 512, 64), (1, 37, 1024, 64),
+                                     (1, 2, 512, 128), (3, 90, 512, 128), (1, 300, 1024, 64)])
+def test_fused_bf16_resident_kernel(B, H, N, d):
+    x = wl.fused_inputs("t", "bf16", B, H, N, d, seed=900 + H + N + d, row_factor=(0.5, 2.5))
     P = gu.run_fused(x, guard=8192)
-    gu.check_weights(gu.to_f64(P), _oracle_heads(x), "bf16", f"resident kernel {B}x{H}x{N}x64")
+    if H <= 40:
+        gu.check_weights(gu.to_f64(P), _oracle_heads(x), "bf16", f"resident kernel {B}x{H}x{N}x{d}")
+    else:   # many heads: a spread of them against the oracle, every row sum
+        got = gu.to_f64(P)
+        for b, h in [(0, 0), (0, 1), (B - 1, H // 2), (B - 1, H - 2), (B - 1, H - 1)]:
+            ref = oracle.attention_weights(x.Q[b, h], x.K[b, h], "bf16", x.scale)
+            gu.check_weights(got[b, h], ref, "bf16", f"resident kernel {B}x{H}x{N}x{d} head ({b},{h})")
+        assert np.abs(got.sum(-1) - 1.0).max() <= gu.ROWSUM_BF16
 
 
-@pytest.mark.parametrize("N", [512, 1024])
-def test_fused_bf16_resident_kernel_negative_scale_and_other_kernels(N, monkeypatch):
-    x = wl.fused_inputs("t", "bf16", 1, 2, N, 64, seed=17 + N, scale=-0.2, row_factor=(0.5, 3.0))
+@pytest.mark.parametrize("N,d", [(512, 64), (1024, 64), (512, 128)])
+def test_fused_bf16_resident_kernel_negative_scale_and_other_kernels(N, d, monkeypatch):
+    x = wl.fused_inputs("t", "bf16", 1, 2, N, d, seed=17 + N + d, scale=-0.2, row_factor=(0.5, 3.0))
     ref = _oracle_heads(x)
     P = gu.run_fused(x, guard=4096)
-    gu.check_weights(gu.to_f64(P), ref, "bf16", f"resident kernel, negative scale, N={N}")
+    gu.check_weights(gu.to_f64(P), ref, "bf16", f"resident kernel, negative scale, N={N} d={d}")
     # the same problem through the round-based and the two-pass kernel
     for which in ("rounds", "twopass"):
         monkeypatch.setenv("ATTNW_FUSED_KERNEL", which)
