@@ -152,41 +152,63 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
             for (int r = 0; r < 16; ++r) acc[qb][r] = 0.0f;
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            if (FAST || 2 * g < cpr_act) {    // wave-uniform: skip the padding of short rows
-                const u32x4 a = *reinterpret_cast<const u32x4*>(rowp + (((2 * g + half) ^ swz) * 16));
+            // padding columns of short rows hold a copy of chunk 0 of the key (finite) and meet zero Q
+            // fragments: no branch here, the loop stays one block the scheduler can interleave
+            const u32x4 a = *reinterpret_cast<const u32x4*>(rowp + (((2 * g + half) ^ swz) * 16));
 #pragma unroll
-                for (int qb = 0; qb < QB; ++qb) Mma<T>::run(acc[qb], a, qf[qb][g]);
-            }
+            for (int qb = 0; qb < QB; ++qb) Mma<T>::run(acc[qb], a, qf[qb][g]);
         }
     };
 
-    // move the wave's staged QW x (32*SUBS) block to global memory, 16 bytes per lane
+    // move the wave's staged QW x (32*SUBS) block to global memory.  Three paths, chosen per wave and
+    // tile (wave-uniform): every row and key of the block exists and rows are 16-byte aligned -> NST
+    // unconditional 16-byte stores past the caches (the output is far larger than the K of a head, which
+    // then stays in L2); aligned rows at an edge -> the same stores predicated; unaligned rows -> one
+    // element per lane, a lane-contiguous run of every staged row.  Returns whether the first path ran:
+    // only then is the number of store instructions issued known to the wait that follows.
     const bool vec_ok = FAST || (N % EPC) == 0;
+    const bool rows_full = FAST || qw0 + QW <= N;
+    // rows that do not start on a 64-byte boundary make every 128-byte piece of a store straddle memory
+    // lines: such stores go through L2, which merges the pieces before they reach HBM
+    const bool past_caches = FAST || (N * ES) % 64 == 0;
     T* const out_lane = out_h + (int64_t)(qw0 + lane / CPS) * N + (lane % CPS) * EPC;
-    auto flush_stage = [&](int kseg0) __attribute__((always_inline)) {
+    auto flush_stage = [&](int kseg0) __attribute__((always_inline)) -> bool {
+        const bool full = FAST || (rows_full && vec_ok && kseg0 + 32 * SUBS <= N);
+        if (full && past_caches) {
 #pragma unroll
-        for (int it = 0; it < QW / RPI; ++it) {
-            const int row = it * RPI + lane / CPS;
-            const u32x4 v = *reinterpret_cast<const u32x4*>(stage + row * ST_PITCH + (lane % CPS) * 16);
-            T* dst = out_lane + (int64_t)(it * RPI) * N + kseg0;
-            if constexpr (FAST) {
-                // past the caches: the output is far larger than the K of a head, which then stays in L2
-                __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(dst));
-            } else {
-                const int q = qw0 + row;
-                const int key0 = kseg0 + (lane % CPS) * EPC;
-                if (q < N && key0 < N) {
-                    if (vec_ok) {
-                        *reinterpret_cast<u32x4*>(dst) = v;
-                    } else {
-                        const T* e = reinterpret_cast<const T*>(&v);
+            for (int it = 0; it < QW / RPI; ++it) {
+                const int row = it * RPI + lane / CPS;
+                const u32x4 v = *reinterpret_cast<const u32x4*>(stage + row * ST_PITCH + (lane % CPS) * 16);
+                __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(out_lane + (int64_t)(it * RPI) * N + kseg0));
+            }
+        } else if (full) {
 #pragma unroll
-                        for (int i = 0; i < EPC; ++i)
-                            if (key0 + i < N) dst[i] = e[i];
-                    }
-                }
+            for (int it = 0; it < QW / RPI; ++it) {
+                const int row = it * RPI + lane / CPS;
+                const u32x4 v = *reinterpret_cast<const u32x4*>(stage + row * ST_PITCH + (lane % CPS) * 16);
+                *reinterpret_cast<u32x4*>(out_lane + (int64_t)(it * RPI) * N + kseg0) = v;
+            }
+        } else if (vec_ok) {
+#pragma unroll
+            for (int it = 0; it < QW / RPI; ++it) {
+                const int row = it * RPI + lane / CPS;
+                const u32x4 v = *reinterpret_cast<const u32x4*>(stage + row * ST_PITCH + (lane % CPS) * 16);
+                if (qw0 + row < N && kseg0 + (lane % CPS) * EPC < N)
+                    *reinterpret_cast<u32x4*>(out_lane + (int64_t)(it * RPI) * N + kseg0) = v;
+            }
+        } else {
+            constexpr int EPR = 32 * SUBS;            // elements of one staged row
+            constexpr int RPE = 64 / EPR;             // staged rows one instruction covers
+            static_assert(EPR <= 64 && QW % RPE == 0, "element store shape");
+#pragma unroll 4
+            for (int it = 0; it < QW / RPE; ++it) {
+                const int row = it * RPE + lane / EPR;
+                const int e = lane % EPR;
+                const T v = *reinterpret_cast<const T*>(stage + row * ST_PITCH + e * ES);
+                if (qw0 + row < N && kseg0 + e < N) out_h[(int64_t)(qw0 + row) * N + kseg0 + e] = v;
             }
         }
+        return full;
     };
     auto stage_put4 = [&](int qb, int u, int r4, float v0, float v1, float v2, float v3) __attribute__((always_inline)) {
         char* p = stage + (qb * 32 + l32) * ST_PITCH + (u * 32 + 8 * r4 + 4 * half) * ES;
@@ -205,10 +227,11 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
 
     // pass one on the scores of one 32-key sub-tile: running maximum and sum of
     // exponentials (Eq. 1), kept per lane; kbase = first key of this lane's first run
-    auto fold_stats = [&](f32x16 (&acc)[QB], int kbase, bool tail) {
+    auto fold_stats = [&](f32x16 (&acc)[QB], int kbase, auto tailc) {
+        constexpr bool tail = decltype(tailc)::value != 0;   // this tile holds keys past N
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
-            if (tail) {
+            if constexpr (tail) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
                     if (kbase + 8 * (r / 4) + (r % 4) >= N) acc[qb][r] = kNegBig;
@@ -227,7 +250,9 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
                 // fp32 results are held to an absolute bound: subtract first so that a
                 // large common offset cancels exactly
                 float e = (ES == 4) ? fast_exp2((acc[qb][r] - mn) * c) : fast_exp2(__builtin_fmaf(acc[qb][r], c, -mb));
-                if (tail && kbase + 8 * (r / 4) + (r % 4) >= N) e = 0.0f;
+                if constexpr (tail) {
+                    if (kbase + 8 * (r / 4) + (r % 4) >= N) e = 0.0f;
+                }
                 sum += e;
             }
             l_run[qb] += sum;
@@ -276,22 +301,27 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
     // Nothing in a body depends on whether a next tile exists: past the end of the sequence
     // the extra DMA re-reads a valid tile and the extra MFMAs chew on stale LDS, both
     // unused -- a branch there would split the block the scheduler interleaves.
-    auto body = [&](int j, auto bufc, auto writec, auto flushc) __attribute__((always_inline)) {
+    auto body = [&](int j, auto bufc, auto writec, auto flushc, auto tailc) __attribute__((always_inline)) {
         constexpr int B = decltype(bufc)::value;
         constexpr bool WRITE = decltype(writec)::value != 0;   // this tile's results go to memory
         constexpr bool FLUSH = decltype(flushc)::value != 0;   // the previous tile's are still staged
         const int k0 = tile_at(j) * BN;
-        const bool tail = !FAST && k0 + BN > N;
-        if constexpr (FLUSH) flush_stage(tile_at(j - 1) * BN + wk * SUBS * 32);
+        bool counted = false;                                  // exactly NST stores were issued by this body
+        if constexpr (FLUSH) counted = flush_stage(tile_at(j - 1) * BN + wk * SUBS * 32);
         static_for<SUBS - 1>([&](auto uc) __attribute__((always_inline)) {
             constexpr int u = decltype(uc)::value;
             mma_subtile(bufc, wk * SUBS + u + 1, acc_of(IC<B * SUBS + u + 1>{}));
             if constexpr (WRITE) emit(acc_of(IC<B * SUBS + u>{}), u);
-            else fold_stats(acc_of(IC<B * SUBS + u>{}), k0 + (wk * SUBS + u) * 32 + 4 * half, tail);
+            else fold_stats(acc_of(IC<B * SUBS + u>{}), k0 + (wk * SUBS + u) * 32 + 4 * half, tailc);
         });
         // The DMA of tile s+1 is older than this body's stores and memory operations
         // retire in order, so the wait can leave the NST stores in flight.
-        if constexpr (FAST && FLUSH) wait_vmem_le<NST>(); else wait_vmem();
+        if constexpr (FAST && FLUSH) {
+            wait_vmem_le<NST>();
+        } else {
+            if (!counted) wait_vmem();
+            wait_vmem_le<NST>();
+        }
         __syncthreads();
         k_issue(tile_at(j + 2 < n_tiles ? j + 2 : j + 2 - n_tiles), bufc);   // this tile's buffer is free now
         // Pin the transfer here: left alone, the scheduler sinks it to the end of the block,
@@ -299,12 +329,21 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
         __builtin_amdgcn_sched_barrier(0);
         mma_subtile(IC<1 - B>{}, wk * SUBS, acc_of(IC<(1 - B) * SUBS>{}));
         if constexpr (WRITE) emit(acc_of(IC<B * SUBS + SUBS - 1>{}), SUBS - 1);
-        else fold_stats(acc_of(IC<B * SUBS + SUBS - 1>{}), k0 + (wk * SUBS + SUBS - 1) * 32 + 4 * half, tail);
+        else fold_stats(acc_of(IC<B * SUBS + SUBS - 1>{}), k0 + (wk * SUBS + SUBS - 1) * 32 + 4 * half, tailc);
+    };
+    // pass-one body of tile j: the instantiation with key masks only where the tile runs past N
+    auto stats_body = [&](int j, auto bufc) __attribute__((always_inline)) {
+        if constexpr (FAST) {
+            body(j, bufc, IC<0>{}, IC<0>{}, IC<0>{});
+        } else {
+            if (tile_at(j) * BN + BN > N) body(j, bufc, IC<0>{}, IC<0>{}, IC<1>{});
+            else body(j, bufc, IC<0>{}, IC<0>{}, IC<0>{});
+        }
     };
 
     if constexpr (!SCORES) {
         // ================= pass one =================================================================
-        for_tiles(0, 0, n_tiles, [&](int j, auto bufc) __attribute__((always_inline)) { body(j, bufc, IC<0>{}, IC<0>{}); });
+        for_tiles(0, 0, n_tiles, stats_body);
 
         // lanes l and l+32 hold the two halves of each query's keys of this wave; the WK
         // waves that share these queries each saw a different slice of every tile
@@ -345,8 +384,8 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
     // ================= pass two (or the only pass of the score GEMM): compute, round, store ========
     // pass one consumed n_tiles buffers, so the first tile of this pass sits in buffer n_tiles & 1
     const int b0 = SCORES ? 0 : (n_tiles & 1);
-    if (b0 == 0) body(0, IC<0>{}, IC<1>{}, IC<0>{}); else body(0, IC<1>{}, IC<1>{}, IC<0>{});
-    for_tiles(1, b0 ^ 1, n_tiles, [&](int j, auto bufc) __attribute__((always_inline)) { body(j, bufc, IC<1>{}, IC<1>{}); });
+    if (b0 == 0) body(0, IC<0>{}, IC<1>{}, IC<0>{}, IC<0>{}); else body(0, IC<1>{}, IC<1>{}, IC<0>{}, IC<0>{});
+    for_tiles(1, b0 ^ 1, n_tiles, [&](int j, auto bufc) __attribute__((always_inline)) { body(j, bufc, IC<1>{}, IC<1>{}, IC<0>{}); });
     wait_vmem();
     flush_stage(tile_at(n_tiles - 1) * BN + wk * SUBS * 32);
 }

@@ -52,22 +52,38 @@ template <> struct Elem<uint16_t> {   // bf16 bit patterns
     static __device__ __forceinline__ void store1(uint16_t* p, float v) { *p = (uint16_t)(pack_bf16x2(v, 0.0f) & 0xffffu); }
 };
 
+// Maximum / sum over the TPR consecutive lanes (a power of two, at most 64) that share a row.
+template <int TPR> __device__ __forceinline__ float lanes_reduce_max(float v)
+{
+#pragma unroll
+    for (int off = (TPR < 64 ? TPR : 64) / 2; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+    return v;
+}
+template <int TPR> __device__ __forceinline__ float lanes_reduce_sum(float v)
+{
+#pragma unroll
+    for (int off = (TPR < 64 ? TPR : 64) / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
 // One row per TPR threads; every thread keeps R groups of E elements of the row in registers
 // (E = the larger of the two types' elements per 16-byte chunk: a group is one chunk of the
-// narrower type and one or two of the wider).  TPR == 64: four rows per 256-thread block,
-// wave-local reductions only.  TPR > 64: one row per block, partial results meet in LDS.
-// Requires cols to be a multiple of E (groups = cols / E <= R * TPR).
+// narrower type and one or two of the wider).  TPR <= 64: 256 / TPR rows per 256-thread block,
+// reductions among the lanes of a row only (short rows share a wave: with one wave per row a
+// 96-byte row would keep 6 of 64 lanes busy).  TPR > 64: one row per block, partial results meet
+// in LDS.  Requires cols to be a multiple of E (groups = cols / E <= R * TPR).
 template <typename TI, typename TO, int R, int TPR>
-__global__ __launch_bounds__(TPR == 64 ? 256 : TPR)
+__global__ __launch_bounds__(TPR <= 64 ? 256 : TPR)
 void softmax_rows_kernel(const TI* S, TO* P, int64_t rows, int groups)   // S == P (in place, TI == TO) is allowed
 {
     constexpr int VI = Elem<TI>::VEC, VO = Elem<TO>::VEC;
     constexpr int E = VI > VO ? VI : VO;
     constexpr int CI = E / VI, CO = E / VO;     // 16-byte chunks per group on the way in / out
-    constexpr int WAVES = (TPR == 64) ? 1 : TPR / 64;
-    const int tid = (TPR == 64) ? (int)(threadIdx.x & 63) : (int)threadIdx.x;
-    const int64_t row = (TPR == 64) ? (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6) : (int64_t)blockIdx.x;
-    if (row >= rows) return;   // whole wave (TPR == 64) or whole block leaves together
+    constexpr int WAVES = (TPR <= 64) ? 1 : TPR / 64;
+    constexpr int RPB = (TPR <= 64) ? 256 / TPR : 1;   // rows per block
+    const int tid = (TPR <= 64) ? (int)(threadIdx.x % TPR) : (int)threadIdx.x;
+    const int64_t row = (TPR <= 64) ? (int64_t)blockIdx.x * RPB + (threadIdx.x / TPR) : (int64_t)blockIdx.x;
+    if (row >= rows) return;   // all lanes of a row (TPR <= 64) or the whole block leave together
 
     const u32x4* src = reinterpret_cast<const u32x4*>(S) + row * groups * CI;
     u32x4* dst = reinterpret_cast<u32x4*>(P) + row * groups * CO;
@@ -99,7 +115,7 @@ void softmax_rows_kernel(const TI* S, TO* P, int64_t rows, int groups)   // S ==
     }
 
     __shared__ float red[2][WAVES];
-    m = wave_reduce_max(m);
+    m = lanes_reduce_max<TPR>(m);
     if constexpr (WAVES > 1) {
         if ((threadIdx.x & 63) == 0) red[0][threadIdx.x >> 6] = m;
         __syncthreads();
@@ -118,7 +134,7 @@ void softmax_rows_kernel(const TI* S, TO* P, int64_t rows, int groups)   // S ==
             l += x[k][i];
         }
     }
-    l = wave_reduce_sum(l);
+    l = lanes_reduce_sum<TPR>(l);
     if constexpr (WAVES > 1) {
         if ((threadIdx.x & 63) == 0) red[1][threadIdx.x >> 6] = l;
         __syncthreads();
@@ -140,26 +156,110 @@ void softmax_rows_kernel(const TI* S, TO* P, int64_t rows, int groups)   // S ==
     }
 }
 
-// Any cols (ragged, unaligned rows, rows too long for registers): one row per
-// 256-thread block, element-wise accesses, the row is read twice.
-template <typename TI, typename TO>
+// Short rows of any length and alignment (cols <= R * TPR): one row per TPR lanes, lane j holds
+// elements j, j + TPR, ... in registers; element-wise accesses (consecutive lanes touch consecutive
+// elements), the row is read once.
+template <typename TI, typename TO, int R, int TPR>
 __global__ __launch_bounds__(256)
-void softmax_generic_kernel(const TI* S, TO* P, int64_t rows, int64_t cols)
+void softmax_elem_kernel(const TI* S, TO* P, int64_t rows, int cols)
 {
-    const int64_t row = blockIdx.x;
+    constexpr int RPB = 256 / TPR;
+    const int tid = (int)(threadIdx.x % TPR);
+    const int64_t row = (int64_t)blockIdx.x * RPB + (threadIdx.x / TPR);
     if (row >= rows) return;
     const TI* src = S + row * cols;
     TO* dst = P + row * cols;
-
-    // online (max, sum): after folding x, l = sum exp(x_k - m) over the k seen so far
-    float m = kNegBig, l = 0.0f;
-    for (int64_t j = threadIdx.x; j < cols; j += 256) {
-        const float x = Elem<TI>::load1(src + j);
-        const float mn = fmaxf(m, x);
-        l = l * fast_exp2((m - mn) * kLog2e) + fast_exp2((x - mn) * kLog2e);
-        m = mn;
+    float x[R];
+    float m = kNegBig;
+#pragma unroll
+    for (int k = 0; k < R; ++k) {
+        const int j = tid + k * TPR;
+        x[k] = j < cols ? Elem<TI>::load1(src + j) : kNegBig;
+        m = fmaxf(m, x[k]);
     }
-    // combine (m, l) pairs across the wave, then across the four waves
+    m = lanes_reduce_max<TPR>(m);
+    float l = 0.0f;
+#pragma unroll
+    for (int k = 0; k < R; ++k) {
+        x[k] = fast_exp2((x[k] - m) * kLog2e);     // absent elements: 2^(-huge) = 0
+        l += x[k];
+    }
+    l = lanes_reduce_sum<TPR>(l);
+    const float inv = 1.0f / l;
+#pragma unroll
+    for (int k = 0; k < R; ++k) {
+        const int j = tid + k * TPR;
+        if (j < cols) Elem<TO>::store1(dst + j, x[k] * inv);
+    }
+}
+
+// Rows that do not fit the registers of a workgroup, and long rows that do not start on 16-byte
+// boundaries.  The row is read twice (statistics, then weights) with 16-byte accesses: the elements of
+// a row in front of its first 16-byte boundary (of both the scores and the weights: they have the same
+// element index) and behind its last whole group are handled one by one.  Few long rows would leave
+// most of the chip idle with one workgroup per row: a row is then cut into `chunks` pieces, one
+// workgroup each; every workgroup gathers the statistics of the WHOLE row itself (the repeated reads
+// are served by the caches) and writes its own piece, so that no partial result has to travel between
+// workgroups.  In place (S == P) needs chunks == 1: another workgroup's statistics pass must not see
+// weights already written.
+template <typename TI, typename TO, int T>      // T threads per workgroup
+__global__ __launch_bounds__(T)
+void softmax_long_kernel(const TI* S, TO* P, int64_t rows, int64_t cols, int chunks)
+{
+    constexpr int VI = Elem<TI>::VEC, VO = Elem<TO>::VEC;
+    constexpr int E = VI > VO ? VI : VO;
+    constexpr int CI = E / VI, CO = E / VO;
+    constexpr int WAVES = T / 64;
+    constexpr int U = 2;                                   // groups in flight per thread
+    const int64_t row = blockIdx.x / (uint32_t)chunks;
+    const int chunk = (int)(blockIdx.x % (uint32_t)chunks);
+    const int tid = (int)threadIdx.x;
+    const TI* src = S + row * cols;
+    TO* dst = P + row * cols;
+    // base pointers are 16-byte aligned: element index (row * cols + j) a multiple of E puts both the
+    // score and the weight of element j on a 16-byte boundary
+    const int64_t head = min(cols, (int64_t)((E - (row * cols) % E) % E));
+    const int64_t ngroups = (cols - head) / E;
+    const int64_t tail0 = head + ngroups * E;
+    const u32x4* vsrc = reinterpret_cast<const u32x4*>(src + head);
+    u32x4* vdst = reinterpret_cast<u32x4*>(dst + head);
+
+    // ---- statistics of the whole row: per-thread running maximum m and l = sum 2^((x - m) log2 e) ----
+    float m = kNegBig, l = 0.0f;
+    auto fold = [&](const float* x, int n) __attribute__((always_inline)) {
+        float gm = x[0];
+#pragma unroll
+        for (int i = 1; i < n; ++i) gm = fmaxf(gm, x[i]);
+        const float mn = fmaxf(m, gm);
+        float sum = 0.0f;
+#pragma unroll
+        for (int i = 0; i < n; ++i) sum += fast_exp2((x[i] - mn) * kLog2e);
+        l = l * fast_exp2((m - mn) * kLog2e) + sum;       // exactly l + sum while the maximum stands
+        m = mn;
+    };
+    for (int64_t g = tid; g < ngroups; g += (int64_t)T * U) {
+        u32x4 raw[U][CI];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t gg = g + (int64_t)u * T;
+            if (gg < ngroups) {
+#pragma unroll
+                for (int j = 0; j < CI; ++j) raw[u][j] = vsrc[gg * CI + j];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (g + (int64_t)u * T < ngroups) {
+                float x[E];
+#pragma unroll
+                for (int j = 0; j < CI; ++j) Elem<TI>::unpack(raw[u][j], x + j * VI);
+                fold(x, E);
+            }
+        }
+    }
+    if (tid < head) { const float x = Elem<TI>::load1(src + tid); fold(&x, 1); }
+    if (tail0 + tid < cols) { const float x = Elem<TI>::load1(src + tail0 + tid); fold(&x, 1); }
+
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
         const float mo = __shfl_xor(m, off, 64), lo = __shfl_xor(l, off, 64);
@@ -167,27 +267,66 @@ void softmax_generic_kernel(const TI* S, TO* P, int64_t rows, int64_t cols)
         l = l * fast_exp2((m - mn) * kLog2e) + lo * fast_exp2((mo - mn) * kLog2e);
         m = mn;
     }
-    __shared__ float sm[4], sl[4];
-    if ((threadIdx.x & 63) == 0) { sm[threadIdx.x >> 6] = m; sl[threadIdx.x >> 6] = l; }
-    __syncthreads();   // also orders every read of pass one before any in-place write below
-    m = fmaxf(fmaxf(sm[0], sm[1]), fmaxf(sm[2], sm[3]));
+    __shared__ float sm[WAVES], sl[WAVES];
+    if ((tid & 63) == 0) { sm[tid >> 6] = m; sl[tid >> 6] = l; }
+    __syncthreads();   // with chunks == 1 also orders every read of the statistics pass before any in-place write
+    m = sm[0];
+#pragma unroll
+    for (int w = 1; w < WAVES; ++w) m = fmaxf(m, sm[w]);
     l = 0.0f;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) l += sl[w] * fast_exp2((sm[w] - m) * kLog2e);
+    for (int w = 0; w < WAVES; ++w) l += sl[w] * fast_exp2((sm[w] - m) * kLog2e);
     const float inv = 1.0f / l;
-    for (int64_t j = threadIdx.x; j < cols; j += 256) {
-        const float x = Elem<TI>::load1(src + j);
-        Elem<TO>::store1(dst + j, fast_exp2((x - m) * kLog2e) * inv);
+
+    // ---- weights of this workgroup's piece of the row ----------------------------------------------------
+    const int64_t g0 = ngroups * chunk / chunks, g1 = ngroups * (chunk + 1) / chunks;
+    for (int64_t g = g0 + tid; g < g1; g += (int64_t)T * U) {
+        u32x4 raw[U][CI];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t gg = g + (int64_t)u * T;
+            if (gg < g1) {
+#pragma unroll
+                for (int j = 0; j < CI; ++j) raw[u][j] = vsrc[gg * CI + j];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t gg = g + (int64_t)u * T;
+            if (gg < g1) {
+                float x[E];
+#pragma unroll
+                for (int j = 0; j < CI; ++j) Elem<TI>::unpack(raw[u][j], x + j * VI);
+#pragma unroll
+                for (int i = 0; i < E; ++i) x[i] = fast_exp2((x[i] - m) * kLog2e) * inv;
+#pragma unroll
+                for (int j = 0; j < CO; ++j) __builtin_nontemporal_store(Elem<TO>::pack(x + j * VO), vdst + gg * CO + j);
+            }
+        }
     }
+    if (chunk == 0 && tid < head)
+        Elem<TO>::store1(dst + tid, fast_exp2((Elem<TI>::load1(src + tid) - m) * kLog2e) * inv);
+    if (chunk == chunks - 1 && tail0 + tid < cols)
+        Elem<TO>::store1(dst + tail0 + tid, fast_exp2((Elem<TI>::load1(src + tail0 + tid) - m) * kLog2e) * inv);
 }
 
 template <typename TI, typename TO, int R, int TPR>
 hipError_t launch_rows(const void* S, void* P, int64_t rows, int groups, hipStream_t stream)
 {
-    const int64_t blocks = (TPR == 64) ? (rows + 3) / 4 : rows;
-    const int threads = (TPR == 64) ? 256 : TPR;
+    constexpr int RPB = (TPR <= 64) ? 256 / TPR : 1;
+    const int64_t blocks = (rows + RPB - 1) / RPB;
+    const int threads = (TPR <= 64) ? 256 : TPR;
     hipLaunchKernelGGL((softmax_rows_kernel<TI, TO, R, TPR>), dim3((uint32_t)blocks), dim3(threads), 0, stream,
                        static_cast<const TI*>(S), static_cast<TO*>(P), rows, groups);
+    return hipGetLastError();
+}
+
+template <typename TI, typename TO, int R, int TPR>
+hipError_t launch_elem(const void* S, void* P, int64_t rows, int cols, hipStream_t stream)
+{
+    constexpr int RPB = 256 / TPR;
+    hipLaunchKernelGGL((softmax_elem_kernel<TI, TO, R, TPR>), dim3((uint32_t)((rows + RPB - 1) / RPB)), dim3(256), 0,
+                       stream, static_cast<const TI*>(S), static_cast<TO*>(P), rows, cols);
     return hipGetLastError();
 }
 
@@ -195,11 +334,14 @@ template <typename TI, typename TO>
 hipError_t launch_softmax_t(const void* S, void* P, int64_t rows, int64_t cols, hipStream_t stream)
 {
     constexpr int E = Elem<TI>::VEC > Elem<TO>::VEC ? Elem<TI>::VEC : Elem<TO>::VEC;
-    // Register-resident rows: up to 8 groups per thread when a group is 8 elements, 4 when both
-    // types are fp32 (a thread's group is 8 resp. 4 fp32 values once unpacked).
-    constexpr int MAXR = (E == 4) ? 4 : 8;
+    // Register-resident rows: a thread keeps up to 64 fp32 values (8 groups of 8 elements, 16 of 4).
+    constexpr int MAXR = 64 / E;
     if (cols % E == 0 && cols / E <= 1024 * MAXR) {
         const int groups = (int)(cols / E);
+        if (groups <= 4) return launch_rows<TI, TO, 1, 4>(S, P, rows, groups, stream);
+        if (groups <= 8) return launch_rows<TI, TO, 1, 8>(S, P, rows, groups, stream);
+        if (groups <= 16) return launch_rows<TI, TO, 1, 16>(S, P, rows, groups, stream);
+        if (groups <= 32) return launch_rows<TI, TO, 1, 32>(S, P, rows, groups, stream);
         if (groups <= 64) return launch_rows<TI, TO, 1, 64>(S, P, rows, groups, stream);
         if (groups <= 128) return launch_rows<TI, TO, 2, 64>(S, P, rows, groups, stream);
         if (groups <= 256) return launch_rows<TI, TO, 4, 64>(S, P, rows, groups, stream);
@@ -207,10 +349,31 @@ hipError_t launch_softmax_t(const void* S, void* P, int64_t rows, int64_t cols, 
         if (groups <= 1024) return launch_rows<TI, TO, 4, 256>(S, P, rows, groups, stream);
         if (groups <= 2048) return launch_rows<TI, TO, 2, 1024>(S, P, rows, groups, stream);
         if (groups <= 4096) return launch_rows<TI, TO, 4, 1024>(S, P, rows, groups, stream);
-        if constexpr (MAXR >= 8) return launch_rows<TI, TO, 8, 1024>(S, P, rows, groups, stream);
+        if constexpr (MAXR >= 16) return launch_rows<TI, TO, 16, 1024>(S, P, rows, groups, stream);
+        else return launch_rows<TI, TO, 8, 1024>(S, P, rows, groups, stream);
     }
-    hipLaunchKernelGGL((softmax_generic_kernel<TI, TO>), dim3((uint32_t)rows), dim3(256), 0, stream,
-                       static_cast<const TI*>(S), static_cast<TO*>(P), rows, cols);
+    // short rows of any length and alignment: in registers, element by element
+    if (cols <= 16) return launch_elem<TI, TO, 1, 16>(S, P, rows, (int)cols, stream);
+    if (cols <= 64) return launch_elem<TI, TO, 1, 64>(S, P, rows, (int)cols, stream);
+    if (cols <= 256) return launch_elem<TI, TO, 4, 64>(S, P, rows, (int)cols, stream);
+    if (cols <= 1024) return launch_elem<TI, TO, 16, 64>(S, P, rows, (int)cols, stream);
+    // everything else: two reads of the row; few rows are cut into pieces so that about one workgroup
+    // per compute unit has work (never in place, and every piece at least 1024 groups long)
+    int64_t chunks = 1;
+    if (S != P) {
+        const int64_t want = (compute_units() + rows - 1) / rows;
+        const int64_t fit = cols / ((int64_t)E * 1024);
+        chunks = want < fit ? want : fit;
+        if (chunks < 1) chunks = 1;
+        if (chunks > 64) chunks = 64;
+    }
+    if (rows * chunks > (int64_t)0x7fffffff) return hipErrorInvalidValue;
+    if (cols / E < 4096)    // a few groups per thread at most: a small workgroup, more of them per compute unit
+        hipLaunchKernelGGL((softmax_long_kernel<TI, TO, 256>), dim3((uint32_t)(rows * chunks)), dim3(256), 0, stream,
+                           static_cast<const TI*>(S), static_cast<TO*>(P), rows, cols, (int)chunks);
+    else
+        hipLaunchKernelGGL((softmax_long_kernel<TI, TO, 1024>), dim3((uint32_t)(rows * chunks)), dim3(1024), 0, stream,
+                           static_cast<const TI*>(S), static_cast<TO*>(P), rows, cols, (int)chunks);
     return hipGetLastError();
 }
 

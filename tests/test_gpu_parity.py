@@ -61,6 +61,28 @@ def test_fused_bf16_small(B, H, N, d):
     gu.check_weights(gu.to_f64(P), _oracle_heads(x), "bf16", f"fused bf16 {B}x{H}x{N}x{d}")
 
 
+# ---- ragged problems of several tiles on the general kernel: interior tiles take the unpredicated
+# store path (past the caches when rows start on 64-byte boundaries: 992; through L2 otherwise: 1000, 500),
+# the last key tile and the last strip the predicated one, odd lengths the element path; 300 heads put
+# the problem on the wide-strip instantiation, d = 96 pads the rows of K in LDS.
+
+@pytest.mark.parametrize("dtype,B,H,N,d", [("bf16", 1, 2, 1000, 128), ("bf16", 1, 2, 992, 64), ("bf16", 1, 1, 777, 64),
+                                           ("bf16", 3, 100, 200, 64), ("bf16", 1, 2, 648, 96), ("bf16", 2, 150, 197, 64),
+                                           ("f32", 1, 2, 500, 64), ("f32", 1, 1, 401, 32)])
+def test_fused_ragged_multi_tile(dtype, B, H, N, d):
+    x = wl.fused_inputs("t", dtype, B, H, N, d, seed=1500 + N + d, row_factor=(0.5, 2.0))
+    P = gu.run_fused(x, guard=8192)
+    got = gu.to_f64(P)
+    if B * H <= 4:
+        gu.check_weights(got, _oracle_heads(x), dtype, f"ragged {dtype} {B}x{H}x{N}x{d}")
+    else:   # many heads: the first, the last and two in the middle against the oracle, row sums everywhere
+        flat = got.reshape(B * H, N, N)
+        for bh in (0, 1, B * H // 2, B * H - 1):
+            ref = oracle.attention_weights(x.Q.reshape(B * H, N, d)[bh], x.K.reshape(B * H, N, d)[bh], dtype, x.scale)
+            gu.check_weights(flat[bh], ref, dtype, f"ragged {dtype} {B}x{H}x{N}x{d} head {bh}")
+        assert np.abs(flat.sum(-1) - 1.0).max() <= (gu.ROWSUM_BF16 if dtype == "bf16" else gu.ROWSUM_F32)
+
+
 # ---- fused bf16, shapes served by the round-based kernel (N a multiple of 256, d = 64 or 128) ---
 # 600 strips over 256 workgroups: strip lists that cross head boundaries; 20 strips: workgroups
 # with one strip (a statistics round followed directly by a weights round) and idle ones;
@@ -181,8 +203,42 @@ def test_softmax_cols(dtype, cols):
     gu.check_weights(gu.to_f64(P), oracle.softmax(s.S, dtype), dtype, f"softmax {dtype} cols={cols}")
 
 
+# Short rows share a wave (4 to 32 lanes per row when rows start on 16-byte boundaries, 16 or 64 lanes
+# with element accesses otherwise): many rows, a row count that leaves the last block partly empty.
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
-@pytest.mark.parametrize("cols", [2048, 1001])
+@pytest.mark.parametrize("cols", [3, 16, 24, 48, 100, 136, 197, 250, 256, 257, 1023])
+def test_softmax_many_short_rows(dtype, cols):
+    rows = 1003
+    s = wl.softmax_inputs("t", dtype, rows, cols, seed=1600 + cols, sigma=2.0, peak_fraction=0.02)
+    P = gu.run_softmax(gu.to_dev(s.S, dtype), rows, cols, dtype, guard=4096)
+    gu.check_weights(gu.to_f64(P), oracle.softmax(s.S, dtype), dtype, f"softmax {dtype} {rows} x {cols}")
+
+
+# Few very long rows: a row is cut into pieces, one workgroup each, every workgroup gathering the
+# statistics of the whole row; odd lengths put the rows off the 16-byte boundaries (scalar head and tail).
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("rows,cols", [(3, 300000), (3, 300001), (2, 1048576 + 24), (5, 99999), (300, 20001)])
+def test_softmax_long_rows(dtype, rows, cols):
+    s = wl.softmax_inputs("t", dtype, rows, cols, seed=1700 + cols % 1000, sigma=2.0, peak_fraction=0.001)
+    P = gu.run_softmax(gu.to_dev(s.S, dtype), rows, cols, dtype, guard=4096)
+    gu.check_weights(gu.to_f64(P), oracle.softmax(s.S, dtype), dtype, f"softmax {dtype} {rows} x {cols}")
+
+
+@pytest.mark.parametrize("src,dst", [("f32", "bf16"), ("bf16", "f32")])
+@pytest.mark.parametrize("rows,cols", [(3, 300001), (1003, 100), (7, 70000)])
+def test_softmax_cast_long_and_short_rows(src, dst, rows, cols):
+    import paper_2407_13885_amd as attnw
+    s = wl.softmax_inputs("t", src, rows, cols, seed=1800 + cols % 1000, sigma=2.0)
+    S = gu.to_dev(s.S, src)
+    P, canary = gu.empty_like_out((rows, cols), dst, guard=4096)
+    attnw.attnw_softmax_cast(S, P, rows, cols, gu.DT[src], gu.DT[dst])
+    torch.cuda.synchronize()
+    assert gu.guards_intact(canary), "softmax wrote outside P"
+    gu.check_weights(gu.to_f64(P), oracle.softmax(s.S, src), dst, f"softmax {src}->{dst} {rows} x {cols}")
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("cols", [2048, 1001, 100, 2049, 70000, 300001])
 def test_softmax_in_place(dtype, cols):
     s = wl.softmax_inputs("t", dtype, 21, cols, seed=500 + cols, sigma=2.0, peak_fraction=0.01)
     S = gu.to_dev(s.S, dtype)
