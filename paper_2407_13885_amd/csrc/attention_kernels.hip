@@ -112,12 +112,13 @@ void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
             qf[qb][g] = *reinterpret_cast<const u32x4*>(Qh + (int64_t)row_in(q0 + qb * 32 + l32) * DB + (2 * g + half) * 16) ^ sign_flip;
 
     // ---- per-lane constants ----------------------------------------------------------------------------
-    int k_key[K_LOADS], k_ch16[K_LOADS];     // K tile transfer j of this lane: key within the tile, byte offset in its row
+    // K tile transfer j of this lane: key within the tile (recomputed where a clamp needs it), byte offset in the tile
+    auto k_key = [&](int j) __attribute__((always_inline)) { return ((wave + NW * j) * 64 + lane) / CPR; };
+    int k_off[K_LOADS];
 #pragma unroll
     for (int j = 0; j < K_LOADS; ++j) {
         const int s = (wave + NW * j) * 64 + lane;
-        k_key[j] = s / CPR;
-        k_ch16[j] = ((s % CPR) ^ ((k_key[j] / C::RPL) & C::SWZ_MASK)) * 16;
+        k_off[j] = k_key(j) * DB + ((s % CPR) ^ ((k_key(j) / C::RPL) & C::SWZ_MASK)) * 16;
     }
     const uint32_t k_lds_base = lds_offset_of(k_lds);
     int kfrag_off[G];
@@ -128,32 +129,42 @@ void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
     }
     // V tile: wave-wide load j covers 64 consecutive keys x one 16-byte chunk (8 output columns); the
     // 8 values go to 8 Vt rows at the key's permuted position (64 lanes -> 128 contiguous bytes per row)
-    int v_key[V_LOADS], v_ch16[V_LOADS], v_ldsoff[V_LOADS];
+    auto v_key = [&](int j) __attribute__((always_inline)) { return ((wave + NW * j) & 1) * 64 + lane; };
+    int v_off[V_LOADS], v_ldsoff[V_LOADS];
 #pragma unroll
     for (int j = 0; j < V_LOADS; ++j) {
-        const int idx = wave + NW * j;
-        const int key = (idx & 1) * 64 + lane;
-        const int ch = idx >> 1;
+        const int key = v_key(j);
+        const int ch = (wave + NW * j) >> 1;
         const int pos = (key & ~12) | ((key & 4) << 1) | ((key & 8) >> 1);   // bits 2 and 3 swapped
-        v_key[j] = key;
-        v_ch16[j] = ch * 16;
+        v_off[j] = key * DB + ch * 16;
         v_ldsoff[j] = ch * 8 * VT_PITCH + pos * 2;
     }
     // Vt fragment of (block dvb, sub-tile u, group m): row dvb*32 + l32, keys u*32 + 16m + 8*half ..
     const int vfrag_off = l32 * VT_PITCH + half * 16;
 
     const int n_tiles = (N + BN - 1) / BN;
+    // rows past the end exist only in the last tile of a TAIL problem: there every row index is clamped
+    // (the row a transfer reads moves, its place in LDS does not)
     auto k_issue = [&](int tile, int buf) __attribute__((always_inline)) {
+        const char* tile_base = Kh + (int64_t)tile * (BN * DB);
+        const bool clamp = TAIL && tile == n_tiles - 1;
 #pragma unroll
-        for (int i = 0; i < K_LOADS; ++i)
-            dma16_untracked(Kh + (int64_t)row_in(tile * BN + k_key[i]) * DB + k_ch16[i],
-                              k_lds_base + buf * K_TILE_BYTES + (wave + NW * i) * 1024);
+        for (int i = 0; i < K_LOADS; ++i) {
+            const char* src = tile_base + k_off[i];
+            if (clamp) src -= (int64_t)(tile * BN + k_key(i) - row_in(tile * BN + k_key(i))) * DB;
+            dma16_untracked(src, k_lds_base + buf * K_TILE_BYTES + (wave + NW * i) * 1024);
+        }
     };
     u32x4 vreg[V_LOADS];
     auto v_load = [&](int tile) __attribute__((always_inline)) {
+        const char* tile_base = Vh + (int64_t)tile * (BN * DB);
+        const bool clamp = TAIL && tile == n_tiles - 1;
 #pragma unroll
-        for (int j = 0; j < V_LOADS; ++j)
-            vreg[j] = *reinterpret_cast<const u32x4*>(Vh + (int64_t)row_in(tile * BN + v_key[j]) * DB + v_ch16[j]);
+        for (int j = 0; j < V_LOADS; ++j) {
+            const char* src = tile_base + v_off[j];
+            if (clamp) src -= (int64_t)(tile * BN + v_key(j) - row_in(tile * BN + v_key(j))) * DB;
+            vreg[j] = *reinterpret_cast<const u32x4*>(src);
+        }
     };
     auto v_scatter = [&](int buf) __attribute__((always_inline)) {
         char* base = vt_lds + buf * VT_BYTES;
@@ -179,8 +190,10 @@ void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
     }
 
     // one 128-key tile out of buffers `buf`
-    auto compute_tile = [&](auto bufc, int t) __attribute__((always_inline)) {
+    // (maskc: the tile runs past N -- only the last tile of a TAIL problem is compiled with the masks)
+    auto compute_tile = [&](auto bufc, int t, auto maskc) __attribute__((always_inline)) {
         constexpr int BUF = decltype(bufc)::value;
+        constexpr bool MASK = decltype(maskc)::value != 0;
         const char* kb = k_lds + BUF * K_TILE_BYTES;
         const char* vb = vt_lds + BUF * VT_BYTES + vfrag_off;
 #pragma unroll
@@ -229,14 +242,12 @@ void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
                 float p[16];
 #pragma unroll
                 for (int r = 0; r < 16; ++r) p[r] = fast_exp2(__builtin_fmaf(s[qb][r], c, -mb));
-                if constexpr (TAIL) {
+                if constexpr (MASK) {
                     // keys past the end were read as key N-1 (their scores change no maximum): no weight
-                    if (t == n_tiles - 1) {
-                        const int kbase = t * BN + u * 32 + 4 * half;
+                    const int kbase = t * BN + u * 32 + 4 * half;
 #pragma unroll
-                        for (int r = 0; r < 16; ++r)
-                            if (kbase + 8 * (r / 4) + (r % 4) >= N) p[r] = 0.0f;
-                    }
+                    for (int r = 0; r < 16; ++r)
+                        if (kbase + 8 * (r / 4) + (r % 4) >= N) p[r] = 0.0f;
                 }
                 float sum = p[0];
 #pragma unroll
@@ -263,22 +274,24 @@ void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
     __syncthreads();
 
     // ---- the sweep: while tile t is computed, K tile t+1 lands in the other buffer and V tile t+1 waits in registers
-    auto iteration = [&](int t, auto bufc) __attribute__((always_inline)) {
+    auto iteration = [&](int t, auto bufc, auto maskc) __attribute__((always_inline)) {
         constexpr int BUF = decltype(bufc)::value;
         const int nxt = t + 1 < n_tiles ? t + 1 : 0;      // past the end: a valid tile, unused
         k_issue(nxt, BUF ^ 1);
         v_load(nxt);
-        compute_tile(bufc, t);
+        compute_tile(bufc, t, maskc);
         v_scatter(BUF ^ 1);
         wait_vmem();
         __syncthreads();
     };
     if constexpr (TAIL) {
-        for_tiles(0, 0, n_tiles, iteration);
+        for_tiles(0, 0, n_tiles - 1, [&](int t, auto bufc) __attribute__((always_inline)) { iteration(t, bufc, IC<0>{}); });
+        if (((n_tiles - 1) & 1) == 0) iteration(n_tiles - 1, IC<0>{}, IC<1>{});
+        else iteration(n_tiles - 1, IC<1>{}, IC<1>{});
     } else {
         for (int t = 0; t < n_tiles; t += 2) {      // N is a multiple of two tiles
-            iteration(t, IC<0>{});
-            iteration(t + 1, IC<1>{});
+            iteration(t, IC<0>{}, IC<0>{});
+            iteration(t + 1, IC<1>{}, IC<0>{});
         }
     }
 
@@ -329,6 +342,9 @@ hipError_t launch_attention(const void* Q, const void* K, const void* V, void* O
 {
     if ((N % 256) != 0) {   // any length: rows past the end are clamped and masked
         if (d == 128) return launch_attention_t<256, 1, true>(Q, K, V, O, BH, (int)N, scale, stream);
+        // (512-query strips only where the rows a last strip leaves unused are a small share)
+        if (N >= 2048 && BH * ((N + 511) / 512) >= 200)
+            return launch_attention_t<128, 2, true>(Q, K, V, O, BH, (int)N, scale, stream);
         return launch_attention_t<128, 1, true>(Q, K, V, O, BH, (int)N, scale, stream);
     }
     if (d == 128) return launch_attention_t<256, 1, false>(Q, K, V, O, BH, (int)N, scale, stream);

@@ -37,9 +37,9 @@ def _run(x, V, guard=4096):
 
 
 def _check_rows(got, x, V, b, h, rows, what):
-    """rows: (r0, r1) range or list of single rows."""
+    """rows: (r0, r1) range or list of single rows and / or ranges."""
     Vw = np.abs(wl.widen(V[b, h], "bf16"))
-    spans = [rows] if isinstance(rows, tuple) else [(r, r + 1) for r in rows]
+    spans = [rows] if isinstance(rows, tuple) else [r if isinstance(r, tuple) else (r, r + 1) for r in rows]
     for r0, r1 in spans:
         ref, P = oracle.attention_output(x.Q[b, h], x.K[b, h], V[b, h], "bf16", x.scale, rows=(r0, r1), return_weights=True)
         A = P @ Vw
@@ -74,6 +74,18 @@ def test_attention_any_length(N, d):
     O = gu.to_f64(_run(x, V))
     for h in range(2):
         _check_rows(O[0, h], x, V, 0, h, (0, N), f"attention N={N} d={d} head {h}")
+
+
+@pytest.mark.parametrize("B,H,N,d", [(1, 40, 2100, 64), (1, 3, 2100, 64), (1, 3, 2300, 128)])
+def test_attention_any_length_long(B, H, N, d):
+    """Ragged lengths of many tiles: only the last tile is compiled with key masks and clamped loads.  40 heads
+    of 2100 queries take the instantiation with two query blocks per wave (512-query strips)."""
+    x = wl.fused_inputs("t", "bf16", B, H, N, d, seed=1900 + H + N + d, row_factor=(0.5, 2.0))
+    V = wl.value_inputs(x, seed=1901 + N)
+    O = gu.to_f64(_run(x, V))
+    assert np.isfinite(O).all()
+    for hh in sorted({0, H // 2, H - 1}):
+        _check_rows(O[0, hh], x, V, 0, hh, [(0, 70), (500, 530), (2040, N)], f"attention {B}x{H}x{N}x{d} head {hh}")
 
 
 def test_attention_any_length_scale_zero_is_the_column_mean():
