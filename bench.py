@@ -273,6 +273,66 @@ def cpu_baseline_softmax(x, rows=8192):
     }
 
 
+# Shapes off the five configurations: ragged lengths, rows of P / S that do not start on 16-, 64- or 128-byte
+# boundaries, head sizes that pad the K rows on chip, many short rows, few very long rows.
+SHAPES_SOFTMAX = [(24576, 2048), (24576, 2047), (24576, 2040), (6000, 8200), (3000, 16385), (768, 65536), (384, 131072),
+                  (96, 524288), (16, 4194304), (100000, 512), (100000, 100), (1000000, 48)]
+SHAPES_QK = [("bf16", 1, 16, 4096, 128), ("bf16", 1, 16, 4096, 64), ("bf16", 1, 16, 4096, 96), ("bf16", 1, 16, 4096, 256),
+             ("bf16", 1, 16, 4000, 128), ("bf16", 1, 16, 4104, 128), ("bf16", 1, 16, 4097, 128), ("bf16", 1, 16, 3968, 64),
+             ("bf16", 8, 16, 640, 64), ("bf16", 64, 16, 128, 64), ("bf16", 64, 16, 197, 64), ("f32", 1, 16, 2048, 64),
+             ("f32", 1, 16, 4000, 64)]
+SHAPES_ATTENTION = [(1, 16, 4096, 128), (1, 16, 4096, 64), (1, 16, 4000, 128), (1, 40, 2100, 64), (8, 16, 512, 64),
+                    (64, 16, 197, 64), (1, 2, 32768, 128)]
+
+
+def bench_shapes(steps, warmup):
+    """Every entry point on the shapes above (random normal inputs made on the device, seed 0; time only --
+    parity on such shapes is what the GPU tests check).  Shorter sections than the configurations get:
+    0.1 s of warm-up, 0.1 s timed unless --steps / --warmup say otherwise."""
+    import torch
+    import paper_2407_13885_amd as attnw
+    global WARM_MS, TIMED_MS
+    WARM_MS, TIMED_MS = 100.0, 100.0
+    torch.manual_seed(0)
+    TD = {"bf16": torch.bfloat16, "f32": torch.float32}
+    DT = {"bf16": attnw.ATTNW_BF16, "f32": attnw.ATTNW_F32}
+    stream = torch.cuda.current_stream()
+    out = []
+    for dt in ("bf16", "f32"):
+        es = 2 if dt == "bf16" else 4
+        for rows, cols in SHAPES_SOFTMAX:
+            S = torch.randn(rows, cols, device="cuda", dtype=TD[dt]) * 2.0
+            P = torch.empty_like(S)
+            _, ev, _, _ = _time_calls(lambda i: attnw.attnw_softmax(S, P, rows, cols, DT[dt], stream), 1, steps, warmup)
+            out.append({"call": "attnw_softmax", "dtype": dt, "rows": rows, "cols": cols, "us": round(ev * 1e3, 1),
+                        "hbm_GBps": round(2 * rows * cols * es / (ev * 1e-3) * 1e-9, 1)})
+            print(f"[bench] {out[-1]}", file=sys.stderr, flush=True)
+            del S, P
+    for dt, B, H, N, d in SHAPES_QK:
+        es = 2 if dt == "bf16" else 4
+        Q = torch.randn(B, H, N, d, device="cuda", dtype=TD[dt])
+        K = torch.randn_like(Q)
+        P = torch.empty(B, H, N, N, device="cuda", dtype=TD[dt])
+        alg = (B * H * N * N + 2 * B * H * N * d) * es
+        for name, fn in (("attnw_fused", attnw.attnw_fused), ("attnw_gemm_scores", attnw.attnw_gemm_scores)):
+            _, ev, _, _ = _time_calls(lambda i: fn(Q, K, P, B, H, N, d, d ** -0.5, DT[dt], stream), 1, steps, warmup)
+            out.append({"call": name, "dtype": dt, "B": B, "H": H, "N": N, "d": d, "us": round(ev * 1e3, 1),
+                        "hbm_GBps": round(alg / (ev * 1e-3) * 1e-9, 1)})
+            print(f"[bench] {out[-1]}", file=sys.stderr, flush=True)
+        del Q, K, P
+    for B, H, N, d in SHAPES_ATTENTION:
+        Q = torch.randn(B, H, N, d, device="cuda", dtype=torch.bfloat16)
+        K, V = torch.randn_like(Q), torch.randn_like(Q)
+        O = torch.empty_like(Q)
+        _, ev, _, _ = _time_calls(lambda i: attnw.attnw_attention(Q, K, V, O, B, H, N, d, d ** -0.5, attnw.ATTNW_BF16, stream),
+                                  1, steps, warmup)
+        out.append({"call": "attnw_attention", "dtype": "bf16", "B": B, "H": H, "N": N, "d": d, "us": round(ev * 1e3, 1),
+                    "mfma_TFLOPs": round(4.0 * B * H * N * N * d / (ev * 1e-3) * 1e-12, 1)})
+        print(f"[bench] {out[-1]}", file=sys.stderr, flush=True)
+        del Q, K, V, O
+    return out
+
+
 def measured_traffic(workload: str, call: str):
     """HBM bytes per launch from the committed rocprofv3 counter summary (profiles/hbm_traffic.txt), or None."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
@@ -300,6 +360,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-unfused", action="store_true", help="skip the unfused pair (score GEMM, then softmax)")
     ap.add_argument("--no-attention", action="store_true", help="skip attnw_attention (O = P V with P kept on chip)")
+    ap.add_argument("--shapes", action="store_true",
+                    help="instead of the configurations, time every entry point on shapes off them (ragged lengths, "
+                         "unaligned rows, padded head sizes, short and very long softmax rows); prints one JSON line")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch one plain elementwise copy of 1 GiB (read 1 GiB, write 1 GiB): the known-size "
                          "kernel that rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -319,6 +382,11 @@ def main() -> int:
         return 2
     attnw.load_library()   # raises if libattnw.so is missing: there is no fallback
     torch.cuda.set_device(0)
+
+    if args.shapes:
+        print(json.dumps({"metric": "time per call on shapes off the configurations", "unit": "us", "n_gpus": 1,
+                          "data": "synthetic", "shapes": bench_shapes(args.steps, args.warmup)}))
+        return 0
 
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
