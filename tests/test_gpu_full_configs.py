@@ -161,3 +161,19 @@ def test_fused_and_attention_at_the_longest_supported_row():
         A = Pr @ Vw
         tol = 2.0 ** -8 * (A + np.abs(ref_o)) * 1.02 + 1e-6 * A
         assert (np.abs(Of[r:r + 1] - ref_o) <= tol).all(), f"attention output row {r} at N = 32768"
+
+
+@pytest.mark.parametrize("N", [65536, 40000])
+def test_fused_beyond_the_round_kernel_lengths(N):
+    """Sequences longer than the round-based kernel takes (N = 65536: P is 8 GiB) and a long ragged one run on
+    the general two-pass kernel: 64-bit row offsets, sampled rows against the oracle, every row sum, and no
+    systematic error of the normaliser over rows of that length."""
+    x = wl.fused_inputs("t", "bf16", 1, 1, N, 64, seed=64 + N % 7, row_factor=(0.5, 2.0))
+    P = gu.run_fused(x)
+    _row_sums_ok(P, gu.ROWSUM_BF16)
+    rows = _sample_rows(x.N, seed=65, n_random=12)
+    got = gu.to_f64(P[0, 0][rows])
+    ref = np.concatenate([oracle.attention_weights(x.Q[0, 0], x.K[0, 0], "bf16", x.scale, rows=(r, r + 1)) for r in rows])
+    gu.check_weights(got, ref, "bf16", f"N = {N} sampled rows")
+    mean_rel = ((got - ref) / np.maximum(ref, 1e-300)).mean(-1)
+    assert float(np.abs(mean_rel).max()) <= 6e-5, f"mean signed relative error of a row {np.abs(mean_rel).max():.2e}"
