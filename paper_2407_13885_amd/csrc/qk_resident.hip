@@ -14,10 +14,11 @@
 // after that a strip costs no K traffic and no waiting on memory:
 //   sweep     wave w owns keys [w N/8, (w+1) N/8) of the row; piece t of them is multiplied with the
 //             strip's 32 queries: S^T = K_piece * Q^T, a lane's 16 accumulators are 16 keys of one query;
-//   local     per lane and wave: maximum of its N/8 scores of a query, then (after the exchange)
-//             e = 2^(c s - c m) in place of the scores and their sum (Softmax section, Eq. 1);
-//   global    the eight waves exchange maxima, then sums, through LDS (two barriers per strip);
-//   weights   p = e / l, rounded once to bf16, staged per wave as [16 queries][64 keys], re-read
+//   local     per lane and wave: maximum m_w of its N/8 scores of a query, e = 2^(c s - c m_w) in place of
+//             the scores and their sum l_w (Softmax section, Eq. 1, against the wave's own maximum);
+//   global    the eight waves exchange (c m_w, l_w) through LDS (one barrier per strip):
+//             m = max m_w, l = sum l_w 2^(c m_w - c m);
+//   weights   p = e 2^(c m_w - c m) / l, rounded once to bf16, staged per wave as [16 queries][64 keys], re-read
 //             16 bytes per lane and stored past the caches (8 rows x 128 bytes per instruction).
 // The Q rows of the next strip are requested before the stores of the current one are issued:
 // vector-memory operations retire in order, and a load behind a burst of stores would wait for it.
@@ -164,7 +165,10 @@ void qk_resident_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restri
     // one strip whose scores are in X; if `ahead`, the scores of the next strip (Q fragments qn) go to Y
     auto strip_body = [&](f32x16 (&X)[NT], f32x16 (&Y)[NT], const u32x4 (&qn)[G], bool ahead, char* out_rows)
                           __attribute__((always_inline)) {
-        // ---- local maximum, exchanged for the global one ------------------------------------------------
+        // ---- local maximum: of this wave's N / NW keys only.  The exponentials are taken against it; the waves
+        //      exchange (reference exponent, local sum) pairs once, after the exponentials, and every wave folds
+        //      the difference to the global maximum into its normalising factor -- one barrier per strip, and
+        //      the exponentials do not wait for the other waves.
         float* const stat_m = stat + parity * (2 * NW * 32);
         float* const stat_l = stat_m + NW * 32;
         float m = kNegBig;
@@ -174,10 +178,6 @@ void qk_resident_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restri
             for (int r = 0; r < 16; r += 2) m = max3(m, X[t][r], X[t][r + 1]);
         }
         m = fmaxf(m, __shfl_xor(m, 32, 64));      // lanes l and l + 32 hold the two halves of a query's keys
-        if (half == 0) stat_m[wave * 32 + l32] = m;
-        __syncthreads();
-#pragma unroll
-        for (int w = 0; w < NW; ++w) m = fmaxf(m, stat_m[w * 32 + l32]);
 
         // ---- exponentials in place of the scores and their local sum; the next strip's sweep rides along ----
         const float mb = m * c;
@@ -211,14 +211,22 @@ void qk_resident_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restri
             }
         }
         l += __shfl_xor(l, 32, 64);
-        if (half == 0) stat_l[wave * 32 + l32] = l;
+        if (half == 0) {
+            stat_m[wave * 32 + l32] = mb;
+            stat_l[wave * 32 + l32] = l;
+        }
         __syncthreads();
-        l = 0.0f;
+        // global reference exponent and sum (Eq. 1 with the maximum taken over all waves); all exponents are
+        // the rounded mb = fl(c * max) the sums were built against, summed in the same order in every wave
+        float mbg = mb;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) l += stat_l[w * 32 + l32];       // same order in every wave
-        const float inv = __builtin_amdgcn_rcpf(l);
-        // The exchange buffers alternate between strips: a wave that is already two barriers ahead writes the
-        // other pair, and cannot get further ahead than that.
+        for (int w = 0; w < NW; ++w) mbg = fmaxf(mbg, stat_m[w * 32 + l32]);
+        float lg = 0.0f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) lg += stat_l[w * 32 + l32] * fast_exp2(stat_m[w * 32 + l32] - mbg);
+        const float inv = fast_exp2(mb - mbg) * __builtin_amdgcn_rcpf(lg);
+        // The exchange buffers alternate between strips: a wave that has passed this barrier writes the other
+        // pair next, and cannot pass the next barrier before every wave has read this one.
         parity ^= 1u;
 
         // ---- weights: scale, round once, stage [ST_ROWS queries][64 keys], store -----------------------

@@ -344,7 +344,8 @@ hipError_t launch_softmax_t(const void* S, void* P, int64_t rows, int64_t cols, 
         if (groups <= 32) return launch_rows<TI, TO, 1, 32>(S, P, rows, groups, stream);
         if (groups <= 64) return launch_rows<TI, TO, 1, 64>(S, P, rows, groups, stream);
         if (groups <= 128) return launch_rows<TI, TO, 2, 64>(S, P, rows, groups, stream);
-        if (groups <= 256) return launch_rows<TI, TO, 4, 64>(S, P, rows, groups, stream);
+        // (two waves per row here: 2 % faster than one wave with four groups per lane on 24576 x 2048 bf16)
+        if (groups <= 256) return launch_rows<TI, TO, 2, 128>(S, P, rows, groups, stream);
         if (groups <= 512) return launch_rows<TI, TO, 2, 256>(S, P, rows, groups, stream);
         if (groups <= 1024) return launch_rows<TI, TO, 4, 256>(S, P, rows, groups, stream);
         if (groups <= 2048) return launch_rows<TI, TO, 2, 1024>(S, P, rows, groups, stream);
