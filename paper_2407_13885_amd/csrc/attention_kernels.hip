@@ -332,7 +332,7 @@ hipError_t launch_attention_t(const void* Q, const void* K, const void* V, void*
 
 bool attention_supported(int64_t BH, int64_t N, int64_t d)
 {
-    if (d != 64 && d != 128) return false;
+    if (d != 32 && d != 64 && d != 128) return false;
     if (N < 1 || N > ((int64_t)1 << 24)) return false;
     return BH * ((N + 255) / 256) <= (int64_t)0x7ffffff0;
 }
@@ -340,6 +340,14 @@ bool attention_supported(int64_t BH, int64_t N, int64_t d)
 hipError_t launch_attention(const void* Q, const void* K, const void* V, void* O, int64_t BH, int64_t N, int64_t d,
                             float scale, hipStream_t stream)
 {
+    if (d == 32) {          // short rows: two query blocks per wave whenever that leaves enough workgroups
+        const bool wide = N >= 2048 && BH * ((N + 511) / 512) >= 200;
+        if ((N % 256) != 0)
+            return wide ? launch_attention_t<64, 2, true>(Q, K, V, O, BH, (int)N, scale, stream)
+                        : launch_attention_t<64, 1, true>(Q, K, V, O, BH, (int)N, scale, stream);
+        return (wide && (N % 512) == 0) ? launch_attention_t<64, 2, false>(Q, K, V, O, BH, (int)N, scale, stream)
+                                        : launch_attention_t<64, 1, false>(Q, K, V, O, BH, (int)N, scale, stream);
+    }
     if ((N % 256) != 0) {   // any length: rows past the end are clamped and masked
         if (d == 128) return launch_attention_t<256, 1, true>(Q, K, V, O, BH, (int)N, scale, stream);
         // (512-query strips only where the rows a last strip leaves unused are a small share)

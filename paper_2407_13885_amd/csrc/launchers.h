@@ -35,7 +35,7 @@ hipError_t launch_qk_resident(const void* Q, const void* K, void* out, int64_t B
 // Y = scale * X over count elements, rounded once to the storage type; X == Y allowed.
 hipError_t launch_scale(DType dt, const void* X, void* Y, int64_t count, float scale, hipStream_t stream);
 
-// Attention output O = softmax(scale Q K^T) V, bf16, d = 64 or 128, N a multiple of 256.
+// Attention output O = softmax(scale Q K^T) V, bf16, d = 32, 64 or 128, any N >= 1.
 bool attention_supported(int64_t BH, int64_t N, int64_t d);
 hipError_t launch_attention(const void* Q, const void* K, const void* V, void* O, int64_t BH, int64_t N, int64_t d,
                             float scale, hipStream_t stream);

@@ -53,7 +53,7 @@ def _check_rows(got, x, V, b, h, rows, what):
 
 
 @pytest.mark.parametrize("B,H,N,d", [(1, 2, 256, 64), (1, 3, 512, 64), (2, 2, 512, 128), (1, 1, 1024, 128),
-                                     (1, 100, 1024, 64)])
+                                     (1, 100, 1024, 64), (1, 3, 512, 32), (1, 100, 2048, 32)])
 def test_attention_bf16_small(B, H, N, d):
     x = wl.fused_inputs("t", "bf16", B, H, N, d, seed=800 + H + N + d)
     V = wl.value_inputs(x, seed=801 + N)
@@ -64,7 +64,7 @@ def test_attention_bf16_small(B, H, N, d):
             _check_rows(O[b, hh], x, V, b, hh, (0, N), f"attention {B}x{H}x{N}x{d} head ({b},{hh})")
 
 
-@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("d", [32, 64, 128])
 @pytest.mark.parametrize("N", [1, 2, 3, 31, 33, 100, 127, 128, 129, 255, 257, 320, 600, 1000])
 def test_attention_any_length(N, d):
     """Lengths that are not whole tiles or strips: rows past the end are clamped on the way in, their
@@ -76,7 +76,7 @@ def test_attention_any_length(N, d):
         _check_rows(O[0, h], x, V, 0, h, (0, N), f"attention N={N} d={d} head {h}")
 
 
-@pytest.mark.parametrize("B,H,N,d", [(1, 40, 2100, 64), (1, 3, 2100, 64), (1, 3, 2300, 128)])
+@pytest.mark.parametrize("B,H,N,d", [(1, 40, 2100, 64), (1, 3, 2100, 64), (1, 3, 2300, 128), (1, 40, 2100, 32)])
 def test_attention_any_length_long(B, H, N, d):
     """Ragged lengths of many tiles: only the last tile is compiled with key masks and clamped loads.  40 heads
     of 2100 queries take the instantiation with two query blocks per wave (512-query strips)."""
