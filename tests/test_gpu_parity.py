@@ -70,7 +70,7 @@ def test_fused_bf16_small(B, H, N, d):
                                            ("bf16", 3, 100, 200, 64), ("bf16", 1, 2, 648, 96), ("bf16", 2, 150, 197, 64),
                                            ("f32", 1, 2, 500, 64), ("f32", 1, 1, 401, 32)])
 def test_fused_ragged_multi_tile(dtype, B, H, N, d):
-    x = wl.fused_inputs("t", dtype, B, H, N, d, seed=1500 + N + d, row_factor=(0.5, 2.0))
+    x = wl.fused_inputs("t", dtype, B, H, N, d, seed=1500 + N + d, row_factor=(0.5, 2.0) if dtype == "bf16" else None)
     P = gu.run_fused(x, guard=8192)
     got = gu.to_f64(P)
     if B * H <= 4:
@@ -372,3 +372,72 @@ def test_calls_from_two_host_threads_on_two_streams():
     assert not errors, errors
     for i in range(2):
         assert torch.equal(outs[i].view(torch.int16), want[i]), f"thread {i}"
+
+
+# ---- seeded random shapes: the boundaries between kernels and instantiations are crossed somewhere ---------
+
+def _random_fused_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        dtype = "bf16" if rng.random() < 0.7 else "f32"
+        d = int(rng.choice([16, 32, 48, 64, 80, 96, 128, 160, 256]))
+        N = int(rng.choice([rng.integers(1, 40), rng.integers(40, 300), rng.integers(300, 900), 256, 512, 640, 768]))
+        BH = int(rng.choice([1, 2, 3, 7, 40, 210])) if N <= 300 else int(rng.choice([1, 2, 5]))
+        B = 1 if BH % 2 or rng.random() < 0.5 else 2
+        scale = float(rng.choice([1.0 / math.sqrt(d), -1.0 / math.sqrt(d), 0.03]))
+        out.append((dtype, B, BH // B, N, d, scale))
+    return out
+
+
+@pytest.mark.parametrize("dtype,B,H,N,d,scale", _random_fused_shapes(36, seed=20240713))
+def test_fused_and_scores_random_shapes(dtype, B, H, N, d, scale):
+    # (fp32: scores of unit spread, which is what the 1e-6 absolute bound belongs to; bf16: sharp and flat rows mixed)
+    x = wl.fused_inputs("t", dtype, B, H, N, d, seed=7000 + 13 * N + d + H, scale=scale,
+                        row_factor=(0.5, 2.0) if dtype == "bf16" else None)
+    P = gu.run_fused(x, guard=4096)
+    got = gu.to_f64(P).reshape(B * H, N, N)
+    Qf, Kf = x.Q.reshape(B * H, N, d), x.K.reshape(B * H, N, d)
+    heads = sorted({0, (B * H) // 2, B * H - 1})
+    abs_f32 = gu.ABS_F32 * max(1.0, abs(scale) * math.sqrt(d))
+    for bh in heads:
+        ref = oracle.attention_weights(Qf[bh], Kf[bh], dtype, x.scale)
+        gu.check_weights(got[bh], ref, dtype, f"random shape {dtype} {B}x{H}x{N}x{d} scale {scale:.3g} head {bh}", abs_f32=abs_f32)
+    rs_tol = gu.ROWSUM_BF16 if dtype == "bf16" else gu.ROWSUM_F32
+    assert np.abs(got.sum(-1) - 1.0).max() <= rs_tol
+    # the score GEMM of the same problem: accumulation bound + one rounding, on the same heads
+    S = gu.to_f64(gu.run_scores(x, guard=4096)).reshape(B * H, N, N)
+    for bh in heads:
+        ref = oracle.scores(Qf[bh], Kf[bh], dtype, x.scale)
+        bound = d * 2.0 ** -24 * abs(scale) * (np.abs(wl.widen(Qf[bh], dtype)) @ np.abs(wl.widen(Kf[bh], dtype)).T)
+        ulp = (2.0 ** -8 if dtype == "bf16" else 2.0 ** -24) * np.abs(ref)
+        assert (np.abs(S[bh] - ref) <= bound + ulp + 1e-30).all(), f"scores {dtype} {B}x{H}x{N}x{d} head {bh}"
+
+
+def _random_softmax_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        src = "bf16" if rng.random() < 0.6 else "f32"
+        dst = src if rng.random() < 0.6 else ("f32" if src == "bf16" else "bf16")
+        cols = int(rng.choice([rng.integers(1, 70), rng.integers(70, 1100), rng.integers(1100, 9000), rng.integers(9000, 80000),
+                               8 * rng.integers(1, 1200), 1024, 2048, 4096]))
+        rows = int(rng.integers(1, 600)) if cols < 9000 else int(rng.integers(1, 12))
+        out.append((src, dst, rows, cols, bool(src == dst and rng.random() < 0.3)))
+    return out
+
+
+@pytest.mark.parametrize("src,dst,rows,cols,inplace", _random_softmax_shapes(40, seed=20240714))
+def test_softmax_random_shapes(src, dst, rows, cols, inplace):
+    import paper_2407_13885_amd as attnw
+    s = wl.softmax_inputs("t", src, rows, cols, seed=9000 + rows + cols, sigma=2.5, peak_fraction=0.01)
+    S = gu.to_dev(s.S, src)
+    if inplace:
+        P, canary = S, None
+    else:
+        P, canary = gu.empty_like_out((rows, cols), dst, guard=4096)
+    attnw.attnw_softmax_cast(S, P, rows, cols, gu.DT[src], gu.DT[dst])
+    torch.cuda.synchronize()
+    if canary is not None:
+        assert gu.guards_intact(canary), "softmax wrote outside P"
+    gu.check_weights(gu.to_f64(P), oracle.softmax(s.S, src), dst, f"softmax {src}->{dst} {rows} x {cols} inplace={inplace}")
