@@ -32,6 +32,11 @@
 // is a weights-only round of its own strip with p = scale * s in place of the exponential, no
 // statistics and no handover (the staging and store path is what makes it worth sharing).
 //
+// Stores: slot A's rounded weights are staged in LDS as [query][key] rows and leave as 16 bytes per lane.  With
+// rows of 128 bytes (d = 64, 128-query strips) two tiles are staged before they are stored, in an area that
+// the two waves which split a tile's keys share: a store instruction then writes 512 contiguous bytes of two
+// rows instead of 128 bytes of eight, which the memory system takes at a higher rate.
+//
 // K tiles travel global -> LDS directly (16 bytes per lane), double buffered.  The transfers are
 // issued from inline assembly so that the only waits on them are the explicit vmcnt waits below:
 // vector-memory operations retire in order, hence "at most n outstanding" with n = the number of
@@ -42,7 +47,11 @@
 namespace attnw {
 namespace {
 
-template <int DB, int WQ, int WK>
+// PAIR: the weights of TWO consecutive tiles are staged before they are stored, in an area shared by the WK = 2
+// waves that split the keys of a tile, so that a store instruction writes 512 contiguous bytes of each of two
+// rows instead of 128 bytes of each of eight (measured store rate of that pattern at N = 16384: 6.3 against
+// 5.5 TB/s).  Costs one more barrier per pair of tiles: the waves read each other's staged rows.
+template <int DB, int WQ, int WK, bool PAIR = false>
 struct RoundsCfg {
     static constexpr int SUBS = 2;                // 32-key sub-tiles per wave per K tile
     static constexpr int NBUF = 2;                // K tile buffers in LDS
@@ -53,12 +62,12 @@ struct RoundsCfg {
     static constexpr int CPR = DB / 16;           // 16-byte chunks per K row
     static constexpr int K_TILE_BYTES = BN * DB;
     static constexpr int LOADS = BN * CPR / 64 / NW;   // 1-KiB wave transfers per wave and tile
-    static constexpr int SEG = 32 * SUBS * 2;     // bytes of one staged row: the wave's keys of one tile
+    static constexpr int SEG = PAIR ? 2 * BN * 2 : 32 * SUBS * 2;   // bytes of one staged row: the wave's keys of one tile, or all keys of two tiles
     static constexpr int ST_PITCH = SEG + 16;
-    static constexpr int ST_BYTES = 32 * ST_PITCH;
+    static constexpr int ST_BYTES = PAIR ? 32 * ST_PITCH / WK : 32 * ST_PITCH;   // per wave (PAIR: a share of the area of its WK waves)
     static constexpr int CPS = SEG / 16;          // chunks per staged row
     static constexpr int RPI = 64 / CPS;          // staged rows one store instruction covers
-    static constexpr int NF = 32 / RPI;           // store instructions per tile and wave
+    static constexpr int NF = PAIR ? 32 / WK / RPI / 2 : 32 / RPI;   // store instructions per tile and wave (PAIR: 32 / WK rows every other tile, half per tile)
     static constexpr int NCH = 2 * G;             // chunks per step (one MFMA each when both slots are live)
     static constexpr int RPL = CPR >= 16 ? 1 : 16 / CPR;
     static constexpr int SWZ_MASK = (CPR >= 16 ? 16 : CPR) - 1;
@@ -68,12 +77,13 @@ struct RoundsCfg {
     static constexpr int LDS_TOTAL = LDS_K + LDS_ST + LDS_STAT;
 };
 
-template <int DB, int WQ, int WK, bool SCORES>
+template <int DB, int WQ, int WK, bool SCORES, bool PAIR = false>
 __global__ __launch_bounds__(64 * WQ * WK)
 void qk_rounds_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, uint16_t* __restrict__ out,
                       int N, float c, uint32_t sign_flip, uint32_t strips_per_head, uint32_t total_strips)
 {
-    using C = RoundsCfg<DB, WQ, WK>;
+    using C = RoundsCfg<DB, WQ, WK, PAIR>;
+    static_assert(!PAIR || WK == 2, "a pair of tiles is staged by the two waves that split a tile's keys");
     constexpr int SUBS = C::SUBS, NBUF = C::NBUF, NW = C::NW, BS = C::BS, BN = C::BN, G = C::G, CPR = C::CPR;
     constexpr int K_TILE_BYTES = C::K_TILE_BYTES, LOADS = C::LOADS, ST_PITCH = C::ST_PITCH;
     constexpr int ST_BYTES = C::ST_BYTES, CPS = C::CPS, RPI = C::RPI, NF = C::NF, NCH = C::NCH;
@@ -119,12 +129,16 @@ void qk_rounds_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
         for (int g = 0; g < G; ++g) frag_off[g] = (wk * SUBS * 32 + l32) * DB + (((2 * g + half) ^ swz) * 16);
     }
     // staging rows of slot A: written as [query][key] runs of 4 keys, read back 16 bytes per lane
-    char* const stage = st_lds + wave * ST_BYTES;
-    const char* const st_rd = stage + (lane / CPS) * ST_PITCH + (lane % CPS) * 16;
-    char* const st_wr = stage + l32 * ST_PITCH + 8 * half;
-    uint32_t out_lane_off[NF];
+    // PAIR: one area of 32 rows per group of WK waves; a wave writes its keys of every row and reads whole rows
+    // 32 / WK * wk .. of it.  Otherwise: a private area per wave.
+    char* const stage = PAIR ? st_lds + wq * (32 * ST_PITCH) : st_lds + wave * ST_BYTES;
+    const int rd_row0 = PAIR ? wk * (32 / WK) : 0;
+    const char* const st_rd = stage + (rd_row0 + lane / CPS) * ST_PITCH + (lane % CPS) * 16;
+    char* const st_wr = stage + l32 * ST_PITCH + (PAIR ? wk * (32 * C::SUBS * 2) : 0) + 8 * half;
+    constexpr int NFL = PAIR ? 2 * NF : NF;       // staged rows a wave holds in registers between read-back and store
+    uint32_t out_lane_off[NFL];
 #pragma unroll
-    for (int f = 0; f < NF; ++f) out_lane_off[f] = (uint32_t)(((f * RPI + lane / CPS) * N + (lane % CPS) * 8) * 2);
+    for (int f = 0; f < NFL; ++f) out_lane_off[f] = (uint32_t)(((rd_row0 + f * RPI + lane / CPS) * N + (lane % CPS) * 8) * 2);
 
     const int n_tiles = N / BN;
 
@@ -142,7 +156,8 @@ void qk_rounds_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
         // Every workgroup starts its sweeps at a different tile and wraps around: with all workgroups
         // marching in step, the rows they write at one moment sit a whole row pitch apart and land on the
         // same few memory channels.
-        const int rot = (int)(((bh * strips_per_head + s0) * 7u) % (uint32_t)n_tiles);
+        // (PAIR: an even rotation keeps the two tiles of a staged pair adjacent and 512-byte aligned in the row)
+        const int rot = (int)(((bh * strips_per_head + s0) * 7u) % (uint32_t)n_tiles) & (PAIR ? ~1 : ~0);
         // K tile of position t of a round's sweep (0 <= t < n_tiles + NBUF: the prefetch runs into the
         // next round, which walks the same rotated order)
         auto tile_at = [&](int t) __attribute__((always_inline)) {
@@ -169,7 +184,7 @@ void qk_rounds_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
         u32x4 kf[G];           // K fragments of the sub-tile whose MFMAs are issued next
         f32x16 accX[2], accY[2];
         float m_run = kNegBig, mb_run = kNegBig, l_run = 0.0f, bias = 0.0f;
-        u32x4 fl[NF];
+        u32x4 fl[NFL];
 
         // ---- segment prologue: the transfers of the previous segment have drained, nobody reads LDS ----
         wait_vmem();
@@ -195,7 +210,8 @@ void qk_rounds_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
                 // Tile t's own buffer was read completely during tile t-1 and takes tile t+NBUF.
                 // Younger than the transfer of tile t+1 are the NF stores of the previous tile's rows --
                 // unless this round has not issued that many yet.
-                if (HAS_A && t >= NBUF) wait_vmem_le<NF>();
+                // (PAIR: the first stores of a round are issued during its third tile)
+                if (HAS_A && t >= NBUF + (PAIR ? 1 : 0)) wait_vmem_le<NF>();
                 else wait_vmem();
                 __syncthreads();
                 k_issue(t + NBUF, BUF);
@@ -208,9 +224,15 @@ void qk_rounds_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
             static_for<NCH>([&](auto cic) __attribute__((always_inline)) {
                 constexpr int ci = decltype(cic)::value;
                 // ---- staged rows of the previous tile: read them all before this step's first staging write
-                if constexpr (HAS_A && U == 0 && FLUSH_PREV && ci == 0) {
+                if constexpr (HAS_A && U == 0 && FLUSH_PREV && ci == 0 && (!PAIR || BUF == 0)) {
 #pragma unroll
-                    for (int f = 0; f < NF; ++f) fl[f] = *reinterpret_cast<const u32x4*>(st_rd + f * RPI * ST_PITCH);
+                    for (int f = 0; f < NFL; ++f) fl[f] = *reinterpret_cast<const u32x4*>(st_rd + f * RPI * ST_PITCH);
+                    if constexpr (PAIR) {
+                        // the rows were written by both waves of the group and the next pair's first write follows
+                        // in this very step: every wave must have its rows in registers first
+                        __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0)
+                        __syncthreads();
+                    }
                 }
                 // ---- slot A: p = 2^(c*s - (c*m + log2 l)), rounded once, 16 / NCH scores per chunk
                 if constexpr (HAS_A) {
@@ -229,7 +251,7 @@ void qk_rounds_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
                     if constexpr (r_end % 4 == 0) {   // a run of 4 consecutive keys is complete
                         constexpr int r4 = r_end / 4 - 1;
                         u32x2 w = {pk[2 * r4], pk[2 * r4 + 1]};
-                        *reinterpret_cast<u32x2*>(st_wr + (U * 32 + 8 * r4) * 2) = w;
+                        *reinterpret_cast<u32x2*>(st_wr + (PAIR ? BUF * (BN * 2) : 0) + (U * 32 + 8 * r4) * 2) = w;
                     }
                 }
                 // ---- slot B: running maximum and sum of exponentials (Eq. 1); chunk 0 folds the maximum
@@ -258,7 +280,8 @@ void qk_rounds_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
                 }
                 // ---- stores of the rows read in chunk 0 (past the caches: the weights are not read again)
                 if constexpr (HAS_A && U == 0 && FLUSH_PREV && ci >= 2 && ci < 2 + NF) {
-                    __builtin_nontemporal_store(fl[ci - 2], reinterpret_cast<u32x4*>(out_prev + out_lane_off[ci - 2]));
+                    constexpr int f = (PAIR ? BUF * NF : 0) + ci - 2;   // PAIR: half of the rows per tile of the following pair
+                    __builtin_nontemporal_store(fl[f], reinterpret_cast<u32x4*>(out_prev + out_lane_off[f]));
                 }
                 // ---- one MFMA of the next sub-tile; once both slots have used fragment g, fetch the same
                 //      fragment of the sub-tile after next (tile t+1, same U)
@@ -281,8 +304,10 @@ void qk_rounds_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
 
         auto tile_body = [&](int t, auto bufc, auto hasac, auto hasbc, auto flushc, char* out_rows) __attribute__((always_inline)) {
             char* out_prev = nullptr;
-            if constexpr (decltype(hasac)::value != 0 && decltype(flushc)::value != 0)
-                out_prev = out_rows + (int64_t)(tile_at(t - 1) * BN + wk * SUBS * 32) * 2;
+            if constexpr (decltype(hasac)::value != 0 && decltype(flushc)::value != 0) {
+                if constexpr (PAIR) out_prev = out_rows + (int64_t)(tile_at(t - 2 - decltype(bufc)::value) * BN) * 2;   // first tile of the pair before
+                else out_prev = out_rows + (int64_t)(tile_at(t - 1) * BN + wk * SUBS * 32) * 2;
+            }
             step(bufc, IC<0>{}, hasac, hasbc, flushc, accX, accY, t, out_prev);
             step(bufc, IC<1>{}, hasac, hasbc, flushc, accY, accX, t, out_prev);
         };
@@ -308,7 +333,7 @@ void qk_rounds_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
             // first group of NBUF tiles: nothing is staged before tile 0
             static_for<NBUF>([&](auto bc) __attribute__((always_inline)) {
                 constexpr int b = decltype(bc)::value;
-                if constexpr (b == 0) tile_body(0, bc, hasac, hasbc, IC<0>{}, out_rows);
+                if constexpr (b == 0 || PAIR) tile_body(b, bc, hasac, hasbc, IC<0>{}, out_rows);
                 else tile_body(b, bc, hasac, hasbc, IC<1>{}, out_rows);
             });
             for (int t = NBUF; t < n_tiles; t += NBUF)
@@ -316,7 +341,19 @@ void qk_rounds_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
                     tile_body(t + decltype(bc)::value, bc, hasac, hasbc, IC<1>{}, out_rows);
                 });
             // rows of the last tile
-            if constexpr (HAS_A) {
+            if constexpr (HAS_A && PAIR) {
+                // the last pair: every wave's rows of it are staged (barrier), then read by the group's other wave;
+                // the second barrier keeps the next round's first staging write behind these reads
+                char* out_prev = out_rows + (int64_t)(tile_at(n_tiles - 2) * BN) * 2;
+                __syncthreads();
+#pragma unroll
+                for (int f = 0; f < NFL; ++f) fl[f] = *reinterpret_cast<const u32x4*>(st_rd + f * RPI * ST_PITCH);
+                __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0)
+                __syncthreads();
+#pragma unroll
+                for (int f = 0; f < NFL; ++f)
+                    __builtin_nontemporal_store(fl[f], reinterpret_cast<u32x4*>(out_prev + out_lane_off[f]));
+            } else if constexpr (HAS_A) {
                 char* out_prev = out_rows + (int64_t)(tile_at(n_tiles - 1) * BN + wk * SUBS * 32) * 2;
 #pragma unroll
                 for (int f = 0; f < NF; ++f) {
@@ -383,10 +420,10 @@ void qk_rounds_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
     wait_vmem();   // no K transfer may be in flight when the workgroup's LDS is released
 }
 
-template <int DB, int WQ, int WK, bool SCORES>
+template <int DB, int WQ, int WK, bool SCORES, bool PAIR = false>
 hipError_t launch_rounds(const void* Q, const void* K, void* out, int64_t BH, int N, float scale, hipStream_t stream)
 {
-    using C = RoundsCfg<DB, WQ, WK>;
+    using C = RoundsCfg<DB, WQ, WK, PAIR>;
     const uint32_t strips_per_head = (uint32_t)(N / C::BS);
     const uint32_t total = (uint32_t)(BH * strips_per_head);
     uint32_t grid = (uint32_t)((compute_units() + 7) / 8 * 8);
@@ -394,7 +431,7 @@ hipError_t launch_rounds(const void* Q, const void* K, void* out, int64_t BH, in
     // weights: exponent scale |scale| log2(e) with the sign folded into Q; scores: the scale itself
     const float c = SCORES ? scale : fabsf(scale) * kLog2e;
     const uint32_t flip = (!SCORES && scale < 0.0f) ? Mma<uint16_t>::kSignMask : 0u;
-    hipLaunchKernelGGL((qk_rounds_kernel<DB, WQ, WK, SCORES>), dim3(grid), dim3(64 * WQ * WK), 0, stream,
+    hipLaunchKernelGGL((qk_rounds_kernel<DB, WQ, WK, SCORES, PAIR>), dim3(grid), dim3(64 * WQ * WK), 0, stream,
                        static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K), static_cast<uint16_t*>(out), N, c,
                        flip, strips_per_head, total);
     return hipGetLastError();
@@ -440,7 +477,9 @@ hipError_t launch_qk_rounds(bool scores_only, const void* Q, const void* K, void
         // problems can afford.  (d = 128 has no LDS for 256-key tiles.)
         const int64_t strips128 = BH * (N / 128);
         if (strips128 < 4 * (int64_t)compute_units() && (N % 512) == 0) return go(IC<128>{}, IC<2>{}, IC<4>{});
-        return go(IC<128>{}, IC<4>{}, IC<2>{});
+        // 128-query strips: the weights of two tiles are staged before they are stored (512-byte runs per row)
+        return scores_only ? launch_rounds<128, 4, 2, true, true>(Q, K, out, BH, (int)N, scale, stream)
+                           : launch_rounds<128, 4, 2, false, true>(Q, K, out, BH, (int)N, scale, stream);
     }
     if (scores_only) return hipErrorInvalidValue;   // the caller keeps scores with 256-byte rows on the general kernel
     return launch_rounds<256, 4, 2, false>(Q, K, out, BH, (int)N, scale, stream);
