@@ -196,13 +196,19 @@ void softmax_elem_kernel(const TI* S, TO* P, int64_t rows, int cols)
 // Rows that do not fit the registers of a workgroup, and long rows that do not start on 16-byte
 // boundaries.  The row is read twice (statistics, then weights) with 16-byte accesses: the elements of
 // a row in front of its first 16-byte boundary (of both the scores and the weights: they have the same
-// element index) and behind its last whole group are handled one by one.  Few long rows would leave
-// most of the chip idle with one workgroup per row: a row is then cut into `chunks` pieces, one
-// workgroup each; every workgroup gathers the statistics of the WHOLE row itself (the repeated reads
-// are served by the caches) and writes its own piece, so that no partial result has to travel between
-// workgroups.  In place (S == P) needs chunks == 1: another workgroup's statistics pass must not see
-// weights already written.
-template <typename TI, typename TO, int T>      // T threads per workgroup
+// element index) and behind its last whole group are handled one by one.
+//
+// MODE 0: one workgroup per row does both passes (the only mode that works in place, S == P).
+// Few long rows would leave most of the chip idle that way: the row is then cut into `chunks` pieces, one
+// workgroup each, and the call becomes two launches on the stream.
+// MODE 1: the statistics (maximum, sum) of each piece.  The pieces of a row have to learn each other's
+//         statistics, and the only memory the call may write is P: the workgroup of piece c stores its
+//         pair into slot c of a small table at the start of EVERY piece's part of P (chunks * 8 bytes,
+//         a piece is at least 16 KiB).
+// MODE 2: the workgroup of a piece reads the table at the start of its OWN part of P -- nobody else reads
+//         or writes that part during this launch -- folds the pairs into the row's maximum and sum, and
+//         overwrites the part, table included, with the weights.
+template <typename TI, typename TO, int T, int MODE>      // T threads per workgroup
 __global__ __launch_bounds__(T)
 void softmax_long_kernel(const TI* S, TO* P, int64_t rows, int64_t cols, int chunks)
 {
@@ -223,8 +229,11 @@ void softmax_long_kernel(const TI* S, TO* P, int64_t rows, int64_t cols, int chu
     const int64_t tail0 = head + ngroups * E;
     const u32x4* vsrc = reinterpret_cast<const u32x4*>(src + head);
     u32x4* vdst = reinterpret_cast<u32x4*>(dst + head);
+    // groups of this workgroup's piece (MODE 0: chunks == 1, the whole row)
+    auto piece_begin = [&](int c) __attribute__((always_inline)) { return ngroups * c / chunks; };
+    const int64_t g0 = piece_begin(chunk), g1 = piece_begin(chunk + 1);
 
-    // ---- statistics of the whole row: per-thread running maximum m and l = sum 2^((x - m) log2 e) ----
+    // ---- statistics: per-thread running maximum m and l = sum 2^((x - m) log2 e) -------------------------
     float m = kNegBig, l = 0.0f;
     auto fold = [&](const float* x, int n) __attribute__((always_inline)) {
         float gm = x[0];
@@ -237,29 +246,39 @@ void softmax_long_kernel(const TI* S, TO* P, int64_t rows, int64_t cols, int chu
         l = l * fast_exp2((m - mn) * kLog2e) + sum;       // exactly l + sum while the maximum stands
         m = mn;
     };
-    for (int64_t g = tid; g < ngroups; g += (int64_t)T * U) {
-        u32x4 raw[U][CI];
+    if constexpr (MODE != 2) {
+        for (int64_t g = g0 + tid; g < g1; g += (int64_t)T * U) {
+            u32x4 raw[U][CI];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t gg = g + (int64_t)u * T;
-            if (gg < ngroups) {
+            for (int u = 0; u < U; ++u) {
+                const int64_t gg = g + (int64_t)u * T;
+                if (gg < g1) {
 #pragma unroll
-                for (int j = 0; j < CI; ++j) raw[u][j] = vsrc[gg * CI + j];
+                    for (int j = 0; j < CI; ++j) raw[u][j] = vsrc[gg * CI + j];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (g + (int64_t)u * T < g1) {
+                    float x[E];
+#pragma unroll
+                    for (int j = 0; j < CI; ++j) Elem<TI>::unpack(raw[u][j], x + j * VI);
+                    fold(x, E);
+                }
             }
         }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if (g + (int64_t)u * T < ngroups) {
-                float x[E];
-#pragma unroll
-                for (int j = 0; j < CI; ++j) Elem<TI>::unpack(raw[u][j], x + j * VI);
-                fold(x, E);
-            }
+        if (chunk == 0 && tid < head) { const float x = Elem<TI>::load1(src + tid); fold(&x, 1); }
+        if (chunk == chunks - 1 && tail0 + tid < cols) { const float x = Elem<TI>::load1(src + tail0 + tid); fold(&x, 1); }
+    } else {
+        // the pairs of all pieces of the row, from the table in this piece's own part of P
+        if (tid < chunks) {
+            const f32x2 pr = reinterpret_cast<const f32x2*>(vdst + g0 * CO)[tid];
+            m = pr[0];
+            l = pr[1];
         }
     }
-    if (tid < head) { const float x = Elem<TI>::load1(src + tid); fold(&x, 1); }
-    if (tail0 + tid < cols) { const float x = Elem<TI>::load1(src + tail0 + tid); fold(&x, 1); }
 
+    // ---- (m, l) pairs of all threads folded into one ------------------------------------------------------
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
         const float mo = __shfl_xor(m, off, 64), lo = __shfl_xor(l, off, 64);
@@ -269,17 +288,26 @@ void softmax_long_kernel(const TI* S, TO* P, int64_t rows, int64_t cols, int chu
     }
     __shared__ float sm[WAVES], sl[WAVES];
     if ((tid & 63) == 0) { sm[tid >> 6] = m; sl[tid >> 6] = l; }
-    __syncthreads();   // with chunks == 1 also orders every read of the statistics pass before any in-place write
+    // also orders every read above (the scores in place, the table in MODE 2) before any write below
+    __syncthreads();
     m = sm[0];
 #pragma unroll
     for (int w = 1; w < WAVES; ++w) m = fmaxf(m, sm[w]);
     l = 0.0f;
 #pragma unroll
     for (int w = 0; w < WAVES; ++w) l += sl[w] * fast_exp2((sm[w] - m) * kLog2e);
+
+    if constexpr (MODE == 1) {
+        // slot `chunk` of the table of every piece of this row
+        if (tid < chunks) {
+            f32x2 pr = {m, l};
+            reinterpret_cast<f32x2*>(vdst + piece_begin(tid) * CO)[chunk] = pr;
+        }
+        return;
+    }
     const float inv = 1.0f / l;
 
     // ---- weights of this workgroup's piece of the row ----------------------------------------------------
-    const int64_t g0 = ngroups * chunk / chunks, g1 = ngroups * (chunk + 1) / chunks;
     for (int64_t g = g0 + tid; g < g1; g += (int64_t)T * U) {
         u32x4 raw[U][CI];
 #pragma unroll
@@ -358,23 +386,29 @@ hipError_t launch_softmax_t(const void* S, void* P, int64_t rows, int64_t cols, 
     if (cols <= 64) return launch_elem<TI, TO, 1, 64>(S, P, rows, (int)cols, stream);
     if (cols <= 256) return launch_elem<TI, TO, 4, 64>(S, P, rows, (int)cols, stream);
     if (cols <= 1024) return launch_elem<TI, TO, 16, 64>(S, P, rows, (int)cols, stream);
-    // everything else: two reads of the row; few rows are cut into pieces so that about one workgroup
-    // per compute unit has work (never in place, and every piece at least 1024 groups long)
+    // everything else: two reads of the row.  Few rows are cut into pieces so that about two workgroups per
+    // compute unit have work (never in place; a piece is at least 2048 groups long: two per thread, and room for
+    // the table of the pieces' statistics at its start)
     int64_t chunks = 1;
-    if (S != P) {
-        const int64_t want = (compute_units() + rows - 1) / rows;
-        const int64_t fit = cols / ((int64_t)E * 1024);
+    if (S != P && rows < compute_units()) {   // (with a row per compute unit the second launch costs more than it gains)
+        const int64_t want = (2 * compute_units() + rows - 1) / rows;
+        const int64_t fit = cols / ((int64_t)E * 2048);
         chunks = want < fit ? want : fit;
         if (chunks < 1) chunks = 1;
-        if (chunks > 64) chunks = 64;
+        if (chunks > 1024) chunks = 1024;
     }
     if (rows * chunks > (int64_t)0x7fffffff) return hipErrorInvalidValue;
-    if (cols / E < 4096)    // a few groups per thread at most: a small workgroup, more of them per compute unit
-        hipLaunchKernelGGL((softmax_long_kernel<TI, TO, 256>), dim3((uint32_t)(rows * chunks)), dim3(256), 0, stream,
-                           static_cast<const TI*>(S), static_cast<TO*>(P), rows, cols, (int)chunks);
-    else
-        hipLaunchKernelGGL((softmax_long_kernel<TI, TO, 1024>), dim3((uint32_t)(rows * chunks)), dim3(1024), 0, stream,
-                           static_cast<const TI*>(S), static_cast<TO*>(P), rows, cols, (int)chunks);
+    const TI* s_ = static_cast<const TI*>(S);
+    TO* p_ = static_cast<TO*>(P);
+    const dim3 grid((uint32_t)(rows * chunks));
+    if (chunks > 1) {
+        hipLaunchKernelGGL((softmax_long_kernel<TI, TO, 1024, 1>), grid, dim3(1024), 0, stream, s_, p_, rows, cols, (int)chunks);
+        hipLaunchKernelGGL((softmax_long_kernel<TI, TO, 1024, 2>), grid, dim3(1024), 0, stream, s_, p_, rows, cols, (int)chunks);
+    } else if (cols / E < 4096) {   // a few groups per thread at most: a small workgroup, more of them per compute unit
+        hipLaunchKernelGGL((softmax_long_kernel<TI, TO, 256, 0>), grid, dim3(256), 0, stream, s_, p_, rows, cols, 1);
+    } else {
+        hipLaunchKernelGGL((softmax_long_kernel<TI, TO, 1024, 0>), grid, dim3(1024), 0, stream, s_, p_, rows, cols, 1);
+    }
     return hipGetLastError();
 }
 

@@ -167,3 +167,33 @@ def test_three_kernel_pipeline_in_a_captured_graph():
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(P.view(torch.int16), want), f"replay {rep}"
+
+
+def test_two_launch_softmax_in_a_captured_graph():
+    """Few very long rows: attnw_softmax is two launches (statistics of the pieces of a row through a table in
+    P, then the weights).  Both are recorded by a stream capture and every replay gives the eager bits, whatever
+    P held before."""
+    rows, cols = 3, 300000
+    s = wl.softmax_inputs("t", "bf16", rows, cols, seed=2200, sigma=2.0, peak_fraction=0.001)
+    S = gu.to_dev(s.S, "bf16")
+    P = torch.empty_like(S)
+    attnw.attnw_softmax(S, P, rows, cols, attnw.ATTNW_BF16, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    want = P.view(torch.int16).clone()
+    gu.check_weights(gu.to_f64(P), oracle.softmax(s.S, "bf16"), "bf16", "two-launch softmax, eager")
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        attnw.attnw_softmax(S, P, rows, cols, attnw.ATTNW_BF16, side)
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            attnw.attnw_softmax(S, P, rows, cols, attnw.ATTNW_BF16, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    for rep in range(3):
+        P.fill_(float(rep) - 1.0)                         # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(P.view(torch.int16), want), f"replay {rep}"
