@@ -277,7 +277,9 @@ def cpu_baseline_softmax(x, rows=8192):
 # boundaries, head sizes that pad the K rows on chip, many short rows, few very long rows.
 SHAPES_SOFTMAX = [(24576, 2048), (24576, 2047), (24576, 2040), (6000, 8200), (3000, 16385), (768, 65536), (384, 131072),
                   (96, 524288), (16, 4194304), (100000, 512), (100000, 100), (1000000, 48)]
-SHAPES_QK = [("bf16", 1, 16, 4096, 128), ("bf16", 1, 16, 4096, 64), ("bf16", 1, 16, 4096, 96), ("bf16", 1, 16, 4096, 256),
+# (first five: one head of n x 128, the sizes of the paper's Table I)
+SHAPES_QK = [("bf16", 1, 1, 1024, 128), ("bf16", 1, 1, 2048, 128), ("bf16", 1, 1, 4096, 128), ("bf16", 1, 1, 8192, 128),
+             ("bf16", 1, 1, 16384, 128), ("bf16", 1, 16, 4096, 128), ("bf16", 1, 16, 4096, 64), ("bf16", 1, 16, 4096, 96), ("bf16", 1, 16, 4096, 256),
              ("bf16", 1, 16, 4000, 128), ("bf16", 1, 16, 4104, 128), ("bf16", 1, 16, 4097, 128), ("bf16", 1, 16, 3968, 64),
              ("bf16", 8, 16, 640, 64), ("bf16", 64, 16, 128, 64), ("bf16", 64, 16, 197, 64), ("f32", 1, 16, 2048, 64),
              ("f32", 1, 16, 4000, 64)]

@@ -22,7 +22,9 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Work is enqueued on it and the call returns without waiting.  A call is
  *     one kernel launch (two for a softmax of few rows too long for the
- *     registers of a workgroup) and nothing else on the stream, so it can be
+ *     registers of a workgroup, and for attention weights of so few heads that
+ *     the keys of a strip are split over workgroups; the first launch then
+ *     uses parts of P as scratch) and nothing else on the stream, so it can be
  *     recorded by stream capture and replayed as part of a graph.
  *   - Return value: ATTNW_OK (0) or a negative attnw_status.  Nothing throws or
  *     aborts.  Arguments are validated before any HIP call, in this order:

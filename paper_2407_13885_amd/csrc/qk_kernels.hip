@@ -40,10 +40,23 @@ namespace {
 // SCORES true: write scale * Q K^T (one pass); false: write the attention weights
 // FAST   true: N is a multiple of the strip and of the K tile and rows are exactly
 //        DB bytes, so no masking, clamping or store predicate is compiled in
-template <typename T, int DB, int QB, int WQ, int WK, int SUBS, bool SCORES, bool FAST>
+// SPLIT  0: a workgroup sweeps all keys of its strip (both passes).
+//        Problems with few strips (one head of a long sequence: the paper's own measurements are
+//        on a single head) would leave most compute units idle that way; their keys are cut into
+//        `kc_count` ranges of whole tiles, one workgroup per (strip, range), and the two passes
+//        become two launches:
+//        1: pass one over the workgroup's key range.  The ranges of a row must learn each other's
+//           (maximum, sum) and the only memory a call may write is the output: the pair of range
+//           k goes into slot k of a small table at the start of the row's piece of EVERY range
+//           (kc_count * 8 bytes; a piece is at least two tiles long).
+//        2: the workgroup reads, for each of its rows, the table at the start of the row's piece
+//           of its OWN range -- nobody else touches that piece during this launch -- folds the
+//           pairs into the row's maximum and sum and runs pass two over its range, overwriting
+//           the tables with weights.  (The score GEMM needs no statistics: one launch of mode 2.)
+template <typename T, int DB, int QB, int WQ, int WK, int SUBS, bool SCORES, bool FAST, int SPLIT = 0>
 __global__ __launch_bounds__(64 * WQ * WK)
 void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__ out,
-               int N, int d, float c, uint32_t sign_flip, uint32_t strips, uint32_t total_tiles)
+               int N, int d, float c, uint32_t sign_flip, uint32_t strips, uint32_t total_tiles, int kc_count)
 {
     constexpr int ES = sizeof(T);
     constexpr int EPC = 16 / ES;              // elements per 16-byte chunk
@@ -71,8 +84,14 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
 
     const uint32_t logical = xcd_contiguous_block_id(blockIdx.x, gridDim.x);
     if (logical >= total_tiles) return;
-    const uint32_t bh = logical / strips;
-    const uint32_t strip = logical - bh * strips;
+    uint32_t unit = logical;              // (head, strip) pair; with SPLIT the key range is the fastest index
+    int kc = 0;
+    if constexpr (SPLIT != 0) {
+        kc = (int)(unit % (uint32_t)kc_count);
+        unit /= (uint32_t)kc_count;
+    }
+    const uint32_t bh = unit / strips;
+    const uint32_t strip = unit - bh * strips;
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6;
@@ -118,13 +137,17 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
         key_of[j] = key;
         goff[j] = key * row_bytes + ch * 16;
     }
-    const int n_tiles = (N + BN - 1) / BN;
+    const int n_tiles_all = (N + BN - 1) / BN;
+    // this workgroup's tiles: t0 .. t0 + n_tiles (all of them without SPLIT)
+    auto range_begin = [&](int k) __attribute__((always_inline)) { return SPLIT != 0 ? n_tiles_all * k / kc_count : 0; };
+    const int t0 = range_begin(kc);
+    const int n_tiles = SPLIT != 0 ? range_begin(kc + 1) - t0 : n_tiles_all;
     // Every workgroup starts its sweep over the keys at a different tile and wraps
     // around.  With all workgroups marching in step, the rows they write at one moment
     // sit a whole row pitch apart and land on the same few memory channels; the
     // stagger spreads the store stream over all of them.
     const int rot = (int)((logical * 7u) % (uint32_t)n_tiles);
-    auto tile_at = [&](int j) __attribute__((always_inline)) { const int t = j + rot; return t >= n_tiles ? t - n_tiles : t; };
+    auto tile_at = [&](int j) __attribute__((always_inline)) { const int t = j + rot; return t0 + (t >= n_tiles ? t - n_tiles : t); };
     auto k_issue = [&](int tile, auto bufc) __attribute__((always_inline)) {
         char* const k_buf = decltype(bufc)::value == 0 ? k_lds0 : k_lds1;
         const int k0 = tile * BN;
@@ -292,8 +315,33 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
         if constexpr ((decltype(slotc)::value & 1) == 0) return acc_a; else return acc_b;
     };
 
+    // (maximum, sum) table of query q in the piece of key range k: 8-byte slots at the start of the piece
+    auto table_of = [&](int q, int k) __attribute__((always_inline)) {
+        return reinterpret_cast<f32x2*>(reinterpret_cast<char*>(out_h) + ((int64_t)q * N + (int64_t)range_begin(k) * BN) * ES);
+    };
+    if constexpr (SPLIT == 2 && !SCORES) {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            const int q = qw0 + qb * 32 + l32;
+            float mn = kNegBig, l = 0.0f;
+            if (FAST || q < N) {
+                const f32x2* tab = table_of(q, kc);
+                for (int k = 0; k < kc_count; ++k) {
+                    const f32x2 pr = tab[k];
+                    const float mx = fmaxf(mn, pr[0]);
+                    l = l * fast_exp2((mn - mx) * c) + pr[1] * fast_exp2((pr[0] - mx) * c);
+                    mn = mx;
+                }
+            } else {
+                l = 1.0f;                     // a row past the end: nothing of it is stored
+            }
+            m_run[qb] = mn;
+            bias[qb] = (ES == 4) ? fast_log2(l) : __builtin_fmaf(mn, c, fast_log2(l));
+        }
+    }
+
     k_issue(tile_at(0), IC<0>{});
-    wait_vmem();
+    wait_vmem();       // (mode 2: also the table reads above -- they must be done before anyone stores)
     __syncthreads();
     k_issue(tile_at(1 % n_tiles), IC<1>{});
     mma_subtile(IC<0>{}, wk * SUBS, acc_of(IC<0>{}));
@@ -341,7 +389,7 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
         }
     };
 
-    if constexpr (!SCORES) {
+    if constexpr (!SCORES && SPLIT != 2) {
         // ================= pass one =================================================================
         for_tiles(0, 0, n_tiles, stats_body);
 
@@ -378,74 +426,135 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
             // bf16: bias = c*m + log2(l) folds max and normaliser into one constant;
             // fp32: the max is subtracted separately, bias = log2(l)
             bias[qb] = (ES == 4) ? fast_log2(l) : __builtin_fmaf(mn, c, fast_log2(l));
+            if constexpr (SPLIT == 1) {
+                // this range's pair into slot kc of the row's table in every range (one lane per query)
+                const int q = qw0 + qb * 32 + l32;
+                if (wk == 0 && half == 0 && (FAST || q < N)) {
+                    const f32x2 pr = {mn, l};
+                    for (int k = 0; k < kc_count; ++k) table_of(q, k)[kc] = pr;
+                }
+            }
         }
+    }
+    if constexpr (SPLIT == 1) {
+        wait_vmem();       // no K transfer may be in flight when the workgroup's LDS is released
+        return;
     }
 
     // ================= pass two (or the only pass of the score GEMM): compute, round, store ========
     // pass one consumed n_tiles buffers, so the first tile of this pass sits in buffer n_tiles & 1
-    const int b0 = SCORES ? 0 : (n_tiles & 1);
+    const int b0 = (SCORES || SPLIT == 2) ? 0 : (n_tiles & 1);
     if (b0 == 0) body(0, IC<0>{}, IC<1>{}, IC<0>{}, IC<0>{}); else body(0, IC<1>{}, IC<1>{}, IC<0>{}, IC<0>{});
     for_tiles(1, b0 ^ 1, n_tiles, [&](int j, auto bufc) __attribute__((always_inline)) { body(j, bufc, IC<1>{}, IC<1>{}, IC<0>{}); });
     wait_vmem();
     flush_stage(tile_at(n_tiles - 1) * BN + wk * SUBS * 32);
 }
 
-template <typename T, int DB, int QB, int WQ, int WK, int SUBS, bool FAST>
-hipError_t launch_variant(bool scores_only, const void* Q, const void* K, void* out, int64_t BH, int N, int d,
-                          float scale, hipStream_t stream)
+// Key ranges per strip for a problem of `units` (head, strip) pairs whose rows have n_tiles K tiles: 1 (no
+// split) when the strips alone give at least half of the compute units a workgroup; else enough ranges of
+// at least two tiles for about two workgroups per compute unit, at most 16 (the table of a row is
+// 8 bytes per range and sits inside the first tile of a piece).
+int key_ranges(int64_t units, int n_tiles)
 {
-    constexpr int BM = 32 * QB * WQ;
+    const int64_t cus = compute_units();
+    if (2 * units >= cus) return 1;
+    int64_t k = (2 * cus + units - 1) / units;
+    if (k > n_tiles / 2) k = n_tiles / 2;
+    if (k > 16) k = 16;
+    return k < 2 ? 1 : (int)k;
+}
+
+template <typename T, int DB, int QB, int WQ, int WK, int SUBS, bool FAST, bool SPLITTABLE>
+hipError_t launch_variant(bool scores_only, const void* Q, const void* K, void* out, int64_t BH, int N, int d,
+                          float scale, hipStream_t stream, bool allow_split)
+{
+    constexpr int BM = 32 * QB * WQ, BN = 32 * SUBS * WK;
     constexpr int threads = 64 * WQ * WK;
     const uint32_t strips = (uint32_t)((N + BM - 1) / BM);
-    const uint64_t total = (uint64_t)BH * strips;
-    const uint32_t grid = (uint32_t)((total + 7) / 8 * 8);
     const T* q = static_cast<const T*>(Q);
     const T* k = static_cast<const T*>(K);
     T* o = static_cast<T*>(out);
-    if (scores_only) {
-        hipLaunchKernelGGL((qk_kernel<T, DB, QB, WQ, WK, SUBS, true, FAST>), dim3(grid), dim3(threads), 0, stream, q, k,
-                           o, N, d, scale, 0u, strips, (uint32_t)total);
-    } else {
-        const float c = fabsf(scale) * kLog2e;
-        const uint32_t flip = scale < 0.0f ? Mma<T>::kSignMask : 0u;
-        hipLaunchKernelGGL((qk_kernel<T, DB, QB, WQ, WK, SUBS, false, FAST>), dim3(grid), dim3(threads), 0, stream, q,
-                           k, o, N, d, c, flip, strips, (uint32_t)total);
+    const float c = scores_only ? scale : fabsf(scale) * kLog2e;
+    const uint32_t flip = (!scores_only && scale < 0.0f) ? Mma<T>::kSignMask : 0u;
+    if constexpr (SPLITTABLE) {
+        // the tables are accessed as pairs of floats: rows of the output must start on 8-byte boundaries
+        const bool aligned8 = scores_only || ((int64_t)N * (int64_t)sizeof(T)) % 8 == 0;
+        const int kc = (aligned8 && allow_split) ? key_ranges(BH * strips, (N + BN - 1) / BN) : 1;
+        if (kc > 1) {
+            const uint64_t total = (uint64_t)BH * strips * kc;
+            if (total > 0x7ffffff0u) return hipErrorInvalidValue;
+            const uint32_t grid = (uint32_t)((total + 7) / 8 * 8);
+            if (scores_only) {
+                hipLaunchKernelGGL((qk_kernel<T, DB, QB, WQ, WK, SUBS, true, FAST, 2>), dim3(grid), dim3(threads), 0,
+                                   stream, q, k, o, N, d, c, flip, strips, (uint32_t)total, kc);
+            } else {
+                hipLaunchKernelGGL((qk_kernel<T, DB, QB, WQ, WK, SUBS, false, FAST, 1>), dim3(grid), dim3(threads), 0,
+                                   stream, q, k, o, N, d, c, flip, strips, (uint32_t)total, kc);
+                hipLaunchKernelGGL((qk_kernel<T, DB, QB, WQ, WK, SUBS, false, FAST, 2>), dim3(grid), dim3(threads), 0,
+                                   stream, q, k, o, N, d, c, flip, strips, (uint32_t)total, kc);
+            }
+            return hipGetLastError();
+        }
     }
+    const uint64_t total = (uint64_t)BH * strips;
+    const uint32_t grid = (uint32_t)((total + 7) / 8 * 8);
+    if (scores_only)
+        hipLaunchKernelGGL((qk_kernel<T, DB, QB, WQ, WK, SUBS, true, FAST>), dim3(grid), dim3(threads), 0, stream, q, k,
+                           o, N, d, c, flip, strips, (uint32_t)total, 1);
+    else
+        hipLaunchKernelGGL((qk_kernel<T, DB, QB, WQ, WK, SUBS, false, FAST>), dim3(grid), dim3(threads), 0, stream, q,
+                           k, o, N, d, c, flip, strips, (uint32_t)total, 1);
     return hipGetLastError();
 }
 
-template <typename T, int DB, int QB, int WQ, int WK, int SUBS>
+template <typename T, int DB, int QB, int WQ, int WK, int SUBS, bool SPLITTABLE = false>
 hipError_t launch_shape(bool scores_only, const void* Q, const void* K, void* out, int64_t BH, int N, int d,
-                        float scale, hipStream_t stream)
+                        float scale, hipStream_t stream, bool allow_split = false)
 {
     constexpr int BM = 32 * QB * WQ, BN = 32 * SUBS * WK;
     // whole strips, whole K tiles, unpadded rows: the variant without masks and predicates
     if (N % BM == 0 && N % BN == 0 && d * (int)sizeof(T) == DB)
-        return launch_variant<T, DB, QB, WQ, WK, SUBS, true>(scores_only, Q, K, out, BH, N, d, scale, stream);
-    return launch_variant<T, DB, QB, WQ, WK, SUBS, false>(scores_only, Q, K, out, BH, N, d, scale, stream);
+        return launch_variant<T, DB, QB, WQ, WK, SUBS, true, SPLITTABLE>(scores_only, Q, K, out, BH, N, d, scale, stream, allow_split);
+    return launch_variant<T, DB, QB, WQ, WK, SUBS, false, SPLITTABLE>(scores_only, Q, K, out, BH, N, d, scale, stream, allow_split);
 }
 
 template <typename T>
 hipError_t launch_qk_t(bool scores_only, const void* Q, const void* K, void* out, int64_t BH, int N, int d,
-                       float scale, hipStream_t stream)
+                       float scale, hipStream_t stream, bool allow_split)
 {
     const int row_bytes = d * (int)sizeof(T);
     constexpr int QB = sizeof(T) == 2 ? 2 : 1;   // fp32 stages twice the bytes per key: half the queries per wave
-    // wide strips (4 waves along the queries) when that still gives every compute unit work
-    const bool big = BH * ((N + 128 * QB - 1) / (128 * QB)) >= 200;
+    // wide strips (4 waves along the queries) when that still gives every compute unit work, also when it
+    // does so only with the keys of a strip split over several workgroups (rows of 128 and 256 bytes)
+    const int64_t wide_units = BH * ((N + 128 * QB - 1) / (128 * QB));
+    const bool big = wide_units >= 200;
+    // (not below 1024 keys: two launches of a few microseconds each cost more than the idle compute units)
+    const bool split = allow_split && !big && N >= 1024 && row_bytes > 64 && row_bytes <= 256 &&
+                       key_ranges(wide_units, (N + 127) / 128) > 1;
     if (row_bytes <= 64)
         return big ? launch_shape<T, 64, QB, 4, 2, 2>(scores_only, Q, K, out, BH, N, d, scale, stream)
                    : launch_shape<T, 64, QB, 1, 2, 2>(scores_only, Q, K, out, BH, N, d, scale, stream);
     if (row_bytes <= 128)
-        return big ? launch_shape<T, 128, QB, 4, 2, 2>(scores_only, Q, K, out, BH, N, d, scale, stream)
-                   : launch_shape<T, 128, QB, 1, 2, 2>(scores_only, Q, K, out, BH, N, d, scale, stream);
+        return (big || split) ? launch_shape<T, 128, QB, 4, 2, 2, true>(scores_only, Q, K, out, BH, N, d, scale, stream, split)
+                              : launch_shape<T, 128, QB, 1, 2, 2>(scores_only, Q, K, out, BH, N, d, scale, stream);
     if (row_bytes <= 256)
-        return big ? launch_shape<T, 256, QB, 4, 2, 2>(scores_only, Q, K, out, BH, N, d, scale, stream)
-                   : launch_shape<T, 256, QB, 1, 2, 2>(scores_only, Q, K, out, BH, N, d, scale, stream);
+        return (big || split) ? launch_shape<T, 256, QB, 4, 2, 2, true>(scores_only, Q, K, out, BH, N, d, scale, stream, split)
+                              : launch_shape<T, 256, QB, 1, 2, 2>(scores_only, Q, K, out, BH, N, d, scale, stream);
     if (row_bytes <= 512) return launch_shape<T, 512, 1, 4, 2, 1>(scores_only, Q, K, out, BH, N, d, scale, stream);
     if constexpr (sizeof(T) == 4)
         return launch_shape<T, 1024, 1, 4, 1, 1>(scores_only, Q, K, out, BH, N, d, scale, stream);
     return hipErrorInvalidValue;   // unreachable: d <= 256 bounds row_bytes
+}
+
+// bf16 shapes the persistent kernels take: those the two-pass kernel with split keys serves better.  Measured
+// on one head of d = 128 (persistent kernel -> split): N = 2048 37 -> 25 us, 4096 68 -> 37, 8192 130 -> 89,
+// 16384 269 -> 223; with 128 strips of 2048 or 4096 keys, and at d = 64 (64-query strips: twice the strips),
+// the persistent kernel is as fast or faster.
+bool prefers_key_split(int64_t BH, int64_t N, int64_t d)
+{
+    if (d != 128 || N < 2048 || (N % 4) != 0) return false;
+    const int64_t strips = BH * ((N + 127) / 128), cus = compute_units();
+    return 4 * strips <= cus || (2 * strips <= cus && N >= 8192);
 }
 
 }  // namespace
@@ -453,20 +562,21 @@ hipError_t launch_qk_t(bool scores_only, const void* Q, const void* K, void* out
 hipError_t launch_qk(DType dt, bool scores_only, const void* Q, const void* K, void* out,
                      int64_t BH, int64_t N, int64_t d, float scale, hipStream_t stream)
 {
-    if (dt == DType::F32) return launch_qk_t<float>(scores_only, Q, K, out, BH, (int)N, (int)d, scale, stream);
+    if (dt == DType::F32) return launch_qk_t<float>(scores_only, Q, K, out, BH, (int)N, (int)d, scale, stream, true);
     // ATTNW_FUSED_KERNEL=twopass keeps bf16 problems on the two-pass kernel above, =rounds keeps short sequences
     // off the resident kernel (tests and measurements compare the three)
     const char* force = getenv("ATTNW_FUSED_KERNEL");
     const bool twopass = force && strcmp(force, "twopass") == 0;
     const bool rounds = force && strcmp(force, "rounds") == 0;
-    if (!twopass) {
+    if (!twopass && !(!rounds && prefers_key_split(BH, N, d))) {
         if (!scores_only && !rounds && qk_resident_supported(BH, N, d))
             return launch_qk_resident(Q, K, out, BH, N, scale, stream);
         // (scores with 256-byte rows stay on the general kernel: two co-resident workgroups of it stream them faster)
         if (qk_rounds_supported(BH, N, d) && (!scores_only || d == 64))
             return launch_qk_rounds(scores_only, Q, K, out, BH, N, d, scale, stream);
     }
-    return launch_qk_t<uint16_t>(scores_only, Q, K, out, BH, (int)N, (int)d, scale, stream);
+    // (forced onto the two-pass kernel: the plain one, a workgroup per strip)
+    return launch_qk_t<uint16_t>(scores_only, Q, K, out, BH, (int)N, (int)d, scale, stream, !twopass);
 }
 
 }  // namespace attnw

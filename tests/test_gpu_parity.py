@@ -441,3 +441,36 @@ def test_softmax_random_shapes(src, dst, rows, cols, inplace):
     if canary is not None:
         assert gu.guards_intact(canary), "softmax wrote outside P"
     gu.check_weights(gu.to_f64(P), oracle.softmax(s.S, src), dst, f"softmax {src}->{dst} {rows} x {cols} inplace={inplace}")
+
+
+# ---- few strips: the keys of a strip are split over several workgroups, statistics through tables in P --------
+
+# (d = 128 on one head: taken from the persistent kernel; the others: shapes of the general kernel)
+@pytest.mark.parametrize("dtype,B,H,N,d,scale", [("bf16", 1, 1, 2048, 128, 0.0884), ("bf16", 1, 1, 4096, 128, -0.0884),
+                                                 ("bf16", 1, 2, 3000, 64, 0.125), ("bf16", 1, 1, 1500, 96, 0.1),
+                                                 ("bf16", 1, 2, 2176, 128, 0.0884), ("f32", 1, 1, 2048, 64, 0.125),
+                                                 ("f32", 1, 2, 1026, 32, 0.17677669)])
+def test_fused_and_scores_with_split_keys(dtype, B, H, N, d, scale):
+    x = wl.fused_inputs("t", dtype, B, H, N, d, seed=8000 + N + d, scale=scale, row_factor=(0.5, 3.0) if dtype == "bf16" else None)
+    P = gu.run_fused(x, guard=8192)
+    got = gu.to_f64(P)
+    rows = sorted({0, 1, 63, 64, 255, 256, N // 2, N - 257, N - 2, N - 1} | set(np.random.default_rng(N).integers(0, N, 24).tolist()))
+    for h in range(H):
+        ref = np.concatenate([oracle.attention_weights(x.Q[0, h], x.K[0, h], dtype, x.scale, rows=(r, r + 1)) for r in rows])
+        gu.check_weights(got[0, h][rows], ref, dtype, f"split keys {dtype} {B}x{H}x{N}x{d} head {h}")
+    rs_tol = gu.ROWSUM_BF16 if dtype == "bf16" else gu.ROWSUM_F32
+    assert np.abs(got.sum(-1) - 1.0).max() <= rs_tol
+    S = gu.to_f64(gu.run_scores(x, guard=8192))
+    for h in range(H):
+        ref = np.concatenate([oracle.scores(x.Q[0, h], x.K[0, h], dtype, x.scale, rows=(r, r + 1)) for r in rows])
+        qa, ka = np.abs(wl.widen(x.Q[0, h], dtype))[rows], np.abs(wl.widen(x.K[0, h], dtype))
+        bound = d * 2.0 ** -24 * abs(scale) * (qa @ ka.T) + (2.0 ** -8 if dtype == "bf16" else 2.0 ** -24) * np.abs(ref) + 1e-30
+        assert (np.abs(S[0, h][rows] - ref) <= bound).all(), f"split-key scores {dtype} {N}x{d} head {h}"
+
+
+def test_split_keys_match_the_unsplit_kernel_bit_for_bit_in_the_scores(monkeypatch):
+    x = wl.fused_inputs("t", "bf16", 1, 1, 2048, 128, seed=8100)
+    a = gu.run_scores(x, guard=4096)
+    monkeypatch.setenv("ATTNW_FUSED_KERNEL", "twopass")     # the plain two-pass kernel: a workgroup per strip
+    b = gu.run_scores(x, guard=4096)
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
