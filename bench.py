@@ -275,7 +275,8 @@ def cpu_baseline_softmax(x, rows=8192):
 
 # Shapes off the five configurations: ragged lengths, rows of P / S that do not start on 16-, 64- or 128-byte
 # boundaries, head sizes that pad the K rows on chip, many short rows, few very long rows.
-SHAPES_SOFTMAX = [(24576, 2048), (24576, 2047), (24576, 2040), (6000, 8200), (3000, 16385), (768, 65536), (384, 131072),
+# (first five: the n x n matrices of the paper's Table I)
+SHAPES_SOFTMAX = [(1024, 1024), (2048, 2048), (4096, 4096), (8192, 8192), (16384, 16384), (24576, 2048), (24576, 2047), (24576, 2040), (6000, 8200), (3000, 16385), (768, 65536), (384, 131072),
                   (96, 524288), (16, 4194304), (100000, 512), (100000, 100), (1000000, 48)]
 # (first five: one head of n x 128, the sizes of the paper's Table I)
 SHAPES_QK = [("bf16", 1, 1, 1024, 128), ("bf16", 1, 1, 2048, 128), ("bf16", 1, 1, 4096, 128), ("bf16", 1, 1, 8192, 128),

@@ -197,3 +197,31 @@ def test_two_launch_softmax_in_a_captured_graph():
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(P.view(torch.int16), want), f"replay {rep}"
+
+
+def test_split_key_fused_in_a_captured_graph():
+    """One head of a long sequence: attnw_fused is two launches (statistics of the key ranges through tables
+    inside P, then the weights).  Recorded by a stream capture, every replay gives the eager bits whatever P held."""
+    N, d = 2048, 128
+    x = wl.fused_inputs("t", "bf16", 1, 1, N, d, seed=2300)
+    Q, K = gu.to_dev(x.Q, "bf16"), gu.to_dev(x.K, "bf16")
+    P = torch.empty((1, 1, N, N), dtype=torch.bfloat16, device="cuda")
+    scale = float(x.scale)
+    attnw.attnw_fused(Q, K, P, 1, 1, N, d, scale, attnw.ATTNW_BF16, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    want = P.view(torch.int16).clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        attnw.attnw_fused(Q, K, P, 1, 1, N, d, scale, attnw.ATTNW_BF16, side)
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            attnw.attnw_fused(Q, K, P, 1, 1, N, d, scale, attnw.ATTNW_BF16, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    for rep in range(3):
+        P.fill_(float(rep) * 7.0 - 3.0)                   # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(P.view(torch.int16), want), f"replay {rep}"
