@@ -49,14 +49,27 @@ def sources() -> list:
 
 
 def build(verbose: bool = False) -> str:
-    """Compile every HIP source for gfx950 into ``libattnw.so`` (always recompiles)."""
+    """Compile every HIP source for gfx950 into ``libattnw.so`` (always recompiles): one hipcc process per
+    source, side by side, objects in a temporary directory, then one link step."""
+    import concurrent.futures
+    import tempfile
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(_ROOT, "include"), "-I", _CSRC, *sources(), "-o", _LIB]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    proc = subprocess.run(cmd, capture_output=True, text=True)
-    if proc.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + proc.stdout + proc.stderr)
+    compile_flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    include = ["-I", os.path.join(_ROOT, "include"), "-I", _CSRC]
+
+    def run(cmd):
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        proc = subprocess.run(cmd, capture_output=True, text=True)
+        if proc.returncode != 0:
+            raise RuntimeError("hipcc failed:\n" + " ".join(cmd) + "\n" + proc.stdout + proc.stderr)
+
+    with tempfile.TemporaryDirectory(prefix="attnw_build_") as tmp:
+        jobs = [(src, os.path.join(tmp, os.path.basename(src) + ".o")) for src in sources()]
+        workers = max(1, min(len(jobs), os.cpu_count() or 1, 8))
+        with concurrent.futures.ThreadPoolExecutor(max_workers=workers) as pool:
+            list(pool.map(lambda j: run([hipcc, *compile_flags, *include, "-c", j[0], "-o", j[1]]), jobs))
+        run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *[o for _, o in jobs], "-o", _LIB])
     global _lib
     _lib = None
     return _LIB
