@@ -529,7 +529,8 @@ hipError_t launch_qk_t(bool scores_only, const void* Q, const void* K, void* out
     const int64_t wide_units = BH * ((N + 128 * QB - 1) / (128 * QB));
     const bool big = wide_units >= 200;
     // (not below 1024 keys: two launches of a few microseconds each cost more than the idle compute units)
-    const bool split = allow_split && !big && N >= 1024 && row_bytes > 64 && row_bytes <= 256 &&
+    const bool tables_fit = scores_only || ((int64_t)N * (int64_t)sizeof(T)) % 8 == 0;   // pairs of floats in rows of P
+    const bool split = allow_split && !big && N >= 1024 && row_bytes > 64 && row_bytes <= 256 && tables_fit &&
                        key_ranges(wide_units, (N + 127) / 128) > 1;
     if (row_bytes <= 64)
         return big ? launch_shape<T, 64, QB, 4, 2, 2>(scores_only, Q, K, out, BH, N, d, scale, stream)
