@@ -315,9 +315,10 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
         if constexpr ((decltype(slotc)::value & 1) == 0) return acc_a; else return acc_b;
     };
 
-    // (maximum, sum) table of query q in the piece of key range k: 8-byte slots at the start of the piece
+    // (maximum, sum) table of query q in the piece of key range k: pairs of floats at the start of the piece
+    // (accessed as single floats: a row of P starts on a 4-byte boundary at least)
     auto table_of = [&](int q, int k) __attribute__((always_inline)) {
-        return reinterpret_cast<f32x2*>(reinterpret_cast<char*>(out_h) + ((int64_t)q * N + (int64_t)range_begin(k) * BN) * ES);
+        return reinterpret_cast<float*>(reinterpret_cast<char*>(out_h) + ((int64_t)q * N + (int64_t)range_begin(k) * BN) * ES);
     };
     if constexpr (SPLIT == 2 && !SCORES) {
 #pragma unroll
@@ -325,11 +326,11 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
             const int q = qw0 + qb * 32 + l32;
             float mn = kNegBig, l = 0.0f;
             if (FAST || q < N) {
-                const f32x2* tab = table_of(q, kc);
+                const float* tab = table_of(q, kc);
                 for (int k = 0; k < kc_count; ++k) {
-                    const f32x2 pr = tab[k];
-                    const float mx = fmaxf(mn, pr[0]);
-                    l = l * fast_exp2((mn - mx) * c) + pr[1] * fast_exp2((pr[0] - mx) * c);
+                    const float pm = tab[2 * k], pl = tab[2 * k + 1];
+                    const float mx = fmaxf(mn, pm);
+                    l = l * fast_exp2((mn - mx) * c) + pl * fast_exp2((pm - mx) * c);
                     mn = mx;
                 }
             } else {
@@ -430,8 +431,11 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
                 // this range's pair into slot kc of the row's table in every range (one lane per query)
                 const int q = qw0 + qb * 32 + l32;
                 if (wk == 0 && half == 0 && (FAST || q < N)) {
-                    const f32x2 pr = {mn, l};
-                    for (int k = 0; k < kc_count; ++k) table_of(q, k)[kc] = pr;
+                    for (int k = 0; k < kc_count; ++k) {
+                        float* tab = table_of(q, k);
+                        tab[2 * kc] = mn;
+                        tab[2 * kc + 1] = l;
+                    }
                 }
             }
         }
@@ -477,9 +481,9 @@ hipError_t launch_variant(bool scores_only, const void* Q, const void* K, void* 
     const float c = scores_only ? scale : fabsf(scale) * kLog2e;
     const uint32_t flip = (!scores_only && scale < 0.0f) ? Mma<T>::kSignMask : 0u;
     if constexpr (SPLITTABLE) {
-        // the tables are accessed as pairs of floats: rows of the output must start on 8-byte boundaries
-        const bool aligned8 = scores_only || ((int64_t)N * (int64_t)sizeof(T)) % 8 == 0;
-        const int kc = (aligned8 && allow_split) ? key_ranges(BH * strips, (N + BN - 1) / BN) : 1;
+        // the tables hold floats: rows of the output must start on 4-byte boundaries
+        const bool aligned4 = scores_only || ((int64_t)N * (int64_t)sizeof(T)) % 4 == 0;
+        const int kc = (aligned4 && allow_split) ? key_ranges(BH * strips, (N + BN - 1) / BN) : 1;
         if (kc > 1) {
             const uint64_t total = (uint64_t)BH * strips * kc;
             if (total > 0x7ffffff0u) return hipErrorInvalidValue;
@@ -529,7 +533,7 @@ hipError_t launch_qk_t(bool scores_only, const void* Q, const void* K, void* out
     const int64_t wide_units = BH * ((N + 128 * QB - 1) / (128 * QB));
     const bool big = wide_units >= 200;
     // (not below 1024 keys: two launches of a few microseconds each cost more than the idle compute units)
-    const bool tables_fit = scores_only || ((int64_t)N * (int64_t)sizeof(T)) % 8 == 0;   // pairs of floats in rows of P
+    const bool tables_fit = scores_only || ((int64_t)N * (int64_t)sizeof(T)) % 4 == 0;   // floats in rows of P
     const bool split = allow_split && !big && N >= 1024 && row_bytes > 64 && row_bytes <= 256 && tables_fit &&
                        key_ranges(wide_units, (N + 127) / 128) > 1;
     if (row_bytes <= 64)
@@ -553,7 +557,7 @@ hipError_t launch_qk_t(bool scores_only, const void* Q, const void* K, void* out
 // the persistent kernel is as fast or faster.
 bool prefers_key_split(int64_t BH, int64_t N, int64_t d)
 {
-    if (d != 128 || N < 2048 || (N % 4) != 0) return false;
+    if (d != 128 || N < 2048 || (N % 2) != 0) return false;
     const int64_t strips = BH * ((N + 127) / 128), cus = compute_units();
     return 4 * strips <= cus || (2 * strips <= cus && N >= 8192);
 }
