@@ -81,7 +81,9 @@ typedef enum {
  * Q, K : [B][H][N][d], read only.         P : [B][H][N][N], written, never read.
  * N >= 1 arbitrary; d a multiple of 16, 16 <= d <= 256; scale any finite float
  * (0 gives the uniform 1/N, negative values are honoured).
- * P must not overlap Q or K.
+ * P must not overlap Q or K.  (So few heads that the strips of queries do not
+ * fill the chip: the keys of a strip are split over workgroups in two launches,
+ * the first of which parks partial row statistics in P.)
  */
 int attnw_fused(const void *Q, const void *K, void *P,
                 int64_t B, int64_t H, int64_t N, int64_t d,
@@ -93,7 +95,9 @@ int attnw_fused(const void *Q, const void *K, void *P,
  *
  * S : [rows][cols], read only.            P : [rows][cols], written.
  * rows, cols >= 1 arbitrary.  P == S exactly (in place) is allowed; any other
- * overlap is ATTNW_ERR_ALIAS.
+ * overlap is ATTNW_ERR_ALIAS.  (Fewer rows than compute units, each longer than
+ * the registers of a workgroup hold, and not in place: two launches, the first
+ * of which parks partial row statistics in P.)
  */
 int attnw_softmax(const void *S, void *P, int64_t rows, int64_t cols,
                   int dtype, void *stream);
