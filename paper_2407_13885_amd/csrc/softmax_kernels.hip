@@ -156,10 +156,40 @@ void softmax_rows_kernel(const TI* S, TO* P, int64_t rows, int groups)   // S ==
     }
 }
 
-// Short rows of any length and alignment (cols <= R * TPR): one row per TPR lanes, lane j holds
-// elements j, j + TPR, ... in registers; element-wise accesses (consecutive lanes touch consecutive
-// elements), the row is read once.
-template <typename TI, typename TO, int R, int TPR>
+// EG consecutive elements of type T (EG * sizeof(T) bytes, naturally aligned) <-> floats
+template <typename T, int EG> __device__ __forceinline__ void load_group(const T* p, float* x)
+{
+    if constexpr (EG == 1) {
+        x[0] = Elem<T>::load1(p);
+    } else if constexpr (sizeof(T) == 2) {            // bf16: 2 or 4 elements = 4 or 8 bytes
+        uint32_t w[EG / 2];
+        if constexpr (EG == 2) w[0] = *reinterpret_cast<const uint32_t*>(p);
+        else { const u32x2 v = *reinterpret_cast<const u32x2*>(p); w[0] = v[0]; w[1] = v[1]; }
+#pragma unroll
+        for (int i = 0; i < EG / 2; ++i) { x[2 * i] = bf16_lo_to_f32(w[i]); x[2 * i + 1] = bf16_hi_to_f32(w[i]); }
+    } else {                                          // fp32: 2 or 4 elements = 8 or 16 bytes
+        if constexpr (EG == 2) { const f32x2 v = *reinterpret_cast<const f32x2*>(p); x[0] = v[0]; x[1] = v[1]; }
+        else { const f32x4 v = *reinterpret_cast<const f32x4*>(p); x[0] = v[0]; x[1] = v[1]; x[2] = v[2]; x[3] = v[3]; }
+    }
+}
+template <typename T, int EG> __device__ __forceinline__ void store_group(T* p, const float* x)
+{
+    if constexpr (EG == 1) {
+        Elem<T>::store1(p, x[0]);
+    } else if constexpr (sizeof(T) == 2) {
+        if constexpr (EG == 2) *reinterpret_cast<uint32_t*>(p) = pack_bf16x2(x[0], x[1]);
+        else { u32x2 v = {pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3])}; *reinterpret_cast<u32x2*>(p) = v; }
+    } else {
+        if constexpr (EG == 2) { f32x2 v = {x[0], x[1]}; *reinterpret_cast<f32x2*>(p) = v; }
+        else { f32x4 v = {x[0], x[1], x[2], x[3]}; *reinterpret_cast<f32x4*>(p) = v; }
+    }
+}
+
+// Short rows whose length is not a whole number of 16-byte chunks of both types (groups = cols / EG <= R * TPR):
+// one row per TPR lanes, lane j holds groups j, j + TPR, ... of EG consecutive elements in registers, EG = the
+// largest of 4, 2, 1 that divides cols (a row then starts on a multiple of EG elements: accesses of EG elements
+// are naturally aligned).  The row is read once.
+template <typename TI, typename TO, int R, int TPR, int EG>
 __global__ __launch_bounds__(256)
 void softmax_elem_kernel(const TI* S, TO* P, int64_t rows, int cols)
 {
@@ -169,27 +199,41 @@ void softmax_elem_kernel(const TI* S, TO* P, int64_t rows, int cols)
     if (row >= rows) return;
     const TI* src = S + row * cols;
     TO* dst = P + row * cols;
-    float x[R];
+    const int groups = cols / EG;
+    float x[R][EG];
     float m = kNegBig;
 #pragma unroll
     for (int k = 0; k < R; ++k) {
-        const int j = tid + k * TPR;
-        x[k] = j < cols ? Elem<TI>::load1(src + j) : kNegBig;
-        m = fmaxf(m, x[k]);
+        const int g = tid + k * TPR;
+        if (g < groups) {
+            load_group<TI, EG>(src + g * EG, x[k]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < EG; ++i) x[k][i] = kNegBig;
+        }
+#pragma unroll
+        for (int i = 0; i < EG; ++i) m = fmaxf(m, x[k][i]);
     }
     m = lanes_reduce_max<TPR>(m);
     float l = 0.0f;
 #pragma unroll
     for (int k = 0; k < R; ++k) {
-        x[k] = fast_exp2((x[k] - m) * kLog2e);     // absent elements: 2^(-huge) = 0
-        l += x[k];
+#pragma unroll
+        for (int i = 0; i < EG; ++i) {
+            x[k][i] = fast_exp2((x[k][i] - m) * kLog2e);     // absent elements: 2^(-huge) = 0
+            l += x[k][i];
+        }
     }
     l = lanes_reduce_sum<TPR>(l);
     const float inv = 1.0f / l;
 #pragma unroll
     for (int k = 0; k < R; ++k) {
-        const int j = tid + k * TPR;
-        if (j < cols) Elem<TO>::store1(dst + j, x[k] * inv);
+        const int g = tid + k * TPR;
+        if (g < groups) {
+#pragma unroll
+            for (int i = 0; i < EG; ++i) x[k][i] *= inv;
+            store_group<TO, EG>(dst + g * EG, x[k]);
+        }
     }
 }
 
@@ -349,13 +393,25 @@ hipError_t launch_rows(const void* S, void* P, int64_t rows, int groups, hipStre
     return hipGetLastError();
 }
 
-template <typename TI, typename TO, int R, int TPR>
+template <typename TI, typename TO, int R, int TPR, int EG>
 hipError_t launch_elem(const void* S, void* P, int64_t rows, int cols, hipStream_t stream)
 {
     constexpr int RPB = 256 / TPR;
-    hipLaunchKernelGGL((softmax_elem_kernel<TI, TO, R, TPR>), dim3((uint32_t)((rows + RPB - 1) / RPB)), dim3(256), 0,
+    hipLaunchKernelGGL((softmax_elem_kernel<TI, TO, R, TPR, EG>), dim3((uint32_t)((rows + RPB - 1) / RPB)), dim3(256), 0,
                        stream, static_cast<const TI*>(S), static_cast<TO*>(P), rows, cols);
     return hipGetLastError();
+}
+
+// cols <= 1024 with cols % EG == 0: lanes per row and groups per lane by the number of groups
+template <typename TI, typename TO, int EG>
+hipError_t launch_elem_groups(const void* S, void* P, int64_t rows, int cols, hipStream_t stream)
+{
+    const int groups = cols / EG;
+    if (groups <= 16) return launch_elem<TI, TO, 1, 16, EG>(S, P, rows, cols, stream);
+    if (groups <= 32) return launch_elem<TI, TO, 1, 32, EG>(S, P, rows, cols, stream);
+    if (groups <= 64) return launch_elem<TI, TO, 1, 64, EG>(S, P, rows, cols, stream);
+    if (groups <= 256) return launch_elem<TI, TO, 4, 64, EG>(S, P, rows, cols, stream);
+    return launch_elem<TI, TO, 16 / EG, 64, EG>(S, P, rows, cols, stream);
 }
 
 template <typename TI, typename TO>
@@ -381,11 +437,12 @@ hipError_t launch_softmax_t(const void* S, void* P, int64_t rows, int64_t cols, 
         if constexpr (MAXR >= 16) return launch_rows<TI, TO, 16, 1024>(S, P, rows, groups, stream);
         else return launch_rows<TI, TO, 8, 1024>(S, P, rows, groups, stream);
     }
-    // short rows of any length and alignment: in registers, element by element
-    if (cols <= 16) return launch_elem<TI, TO, 1, 16>(S, P, rows, (int)cols, stream);
-    if (cols <= 64) return launch_elem<TI, TO, 1, 64>(S, P, rows, (int)cols, stream);
-    if (cols <= 256) return launch_elem<TI, TO, 4, 64>(S, P, rows, (int)cols, stream);
-    if (cols <= 1024) return launch_elem<TI, TO, 16, 64>(S, P, rows, (int)cols, stream);
+    // short rows of any length and alignment: in registers, in groups of 4, 2 or 1 elements
+    if (cols <= 1024) {
+        if (cols % 4 == 0) return launch_elem_groups<TI, TO, 4>(S, P, rows, (int)cols, stream);
+        if (cols % 2 == 0) return launch_elem_groups<TI, TO, 2>(S, P, rows, (int)cols, stream);
+        return launch_elem_groups<TI, TO, 1>(S, P, rows, (int)cols, stream);
+    }
     // everything else: two reads of the row.  Few rows are cut into pieces so that about two workgroups per
     // compute unit have work (never in place; a piece is at least 2048 groups long: two per thread, and room for
     // the table of the pieces' statistics at its start)
