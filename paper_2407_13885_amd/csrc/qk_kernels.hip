@@ -220,16 +220,31 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
                     *reinterpret_cast<u32x4*>(out_lane + (int64_t)(it * RPI) * N + kseg0) = v;
             }
         } else {
-            constexpr int EPR = 32 * SUBS;            // elements of one staged row
-            constexpr int RPE = 64 / EPR;             // staged rows one instruction covers
-            static_assert(EPR <= 64 && QW % RPE == 0, "element store shape");
+            // rows off the 16-byte boundaries: groups of GB = 8, 4 or sizeof(T) bytes, the largest that the row
+            // length is a multiple of (rows then start on multiples of it); a lane-contiguous run of every staged row
+            auto store_groups = [&](auto gbc) __attribute__((always_inline)) {
+                constexpr int GB = decltype(gbc)::value;          // bytes per lane
+                constexpr int EG = GB / ES;                       // elements per lane
+                constexpr int LPR = SEG / GB;                     // lanes per staged row
+                constexpr int RPE = 64 / LPR;                     // staged rows one instruction covers
+                static_assert(LPR <= 64 && QW % RPE == 0, "group store shape");
 #pragma unroll 4
-            for (int it = 0; it < QW / RPE; ++it) {
-                const int row = it * RPE + lane / EPR;
-                const int e = lane % EPR;
-                const T v = *reinterpret_cast<const T*>(stage + row * ST_PITCH + e * ES);
-                if (qw0 + row < N && kseg0 + e < N) out_h[(int64_t)(qw0 + row) * N + kseg0 + e] = v;
-            }
+                for (int it = 0; it < QW / RPE; ++it) {
+                    const int row = it * RPE + lane / LPR;
+                    const int e = (lane % LPR) * EG;
+                    const char* from = stage + row * ST_PITCH + e * ES;
+                    T* to = out_h + (int64_t)(qw0 + row) * N + kseg0 + e;
+                    if (qw0 + row < N && kseg0 + e < N) {         // (N is a multiple of EG: a group is inside or outside)
+                        if constexpr (GB == 8) *reinterpret_cast<u32x2*>(to) = *reinterpret_cast<const u32x2*>(from);
+                        else if constexpr (GB == 4) *reinterpret_cast<uint32_t*>(to) = *reinterpret_cast<const uint32_t*>(from);
+                        else *to = *reinterpret_cast<const T*>(from);
+                    }
+                }
+            };
+            const int row_bytes_out = N * ES;
+            if (row_bytes_out % 8 == 0) store_groups(IC<8>{});
+            else if (ES == 2 && row_bytes_out % 4 == 0) store_groups(IC<4>{});
+            else store_groups(IC<ES>{});
         }
         return full;
     };
