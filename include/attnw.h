@@ -65,7 +65,7 @@ typedef enum {
     ATTNW_ERR_NULL = -1,        /* a required pointer is NULL */
     ATTNW_ERR_SHAPE = -2,       /* a negative dimension, or a product that overflows int64 */
     ATTNW_ERR_DTYPE = -3,       /* dtype is neither ATTNW_F32 nor ATTNW_BF16 */
-    ATTNW_ERR_UNSUPPORTED = -4, /* d not a multiple of 16 or above 256; a dimension beyond the 32-bit grid limits */
+    ATTNW_ERR_UNSUPPORTED = -4, /* d not a multiple of 16 (bf16) / 4 (fp32) or above 256; a dimension beyond the 32-bit grid limits */
     ATTNW_ERR_ALIGN = -5,       /* a base pointer is not 16-byte aligned */
     ATTNW_ERR_ALIAS = -6,       /* output overlaps an input */
     ATTNW_ERR_LAUNCH = -7       /* the HIP runtime refused the launch */
@@ -78,12 +78,16 @@ typedef enum {
  *   P[b][h][i][j] = exp(s_ij - m_i) / sum_k exp(s_ik - m_i),
  *   s_ij = scale * sum_t Q[b][h][i][t] * K[b][h][j][t],   m_i = max_j s_ij.
  *
- * Q, K : [B][H][N][d], read only.         P : [B][H][N][N], written, never read.
- * N >= 1 arbitrary; d a multiple of 16, 16 <= d <= 256; scale any finite float
- * (0 gives the uniform 1/N, negative values are honoured).
- * P must not overlap Q or K.  (So few heads that the strips of queries do not
- * fill the chip: the keys of a strip are split over workgroups in two launches,
- * the first of which parks partial row statistics in P.)
+ * Q, K : [B][H][N][d], read only.         P : [B][H][N][N], written.
+ * N >= 1 arbitrary; d <= 256 and a multiple of 16 (bf16) or of 4 (fp32): rows of
+ * Q and K are whole 16-byte chunks; scale any finite float (0 gives the uniform
+ * 1/N, negative values are honoured).  P must not overlap Q or K.
+ * P is the only memory a call writes, and for some shapes it doubles as the
+ * exchange area while the call runs: workgroups that share the keys of a row
+ * park partial row statistics (maximum, sum) in parts of P that the same call
+ * overwrites with weights before it completes, and read them back from there.
+ * What P held before the call is never used; after the call every element of
+ * P is a weight.
  */
 int attnw_fused(const void *Q, const void *K, void *P,
                 int64_t B, int64_t H, int64_t N, int64_t d,
@@ -142,9 +146,10 @@ int attnw_scale(const void *X, void *Y, int64_t count, float scale,
                 int dtype, void *stream);
 
 /*
- * Attention output with the weights kept on chip (the product the paper's
- * Conclusion names as the next thing to fuse: Attention(Q, K, V) =
- * softmax(Q K^T / sqrt(d_k)) V, Multi-Head Self-Attention section):
+ * Attention output with the weights kept on chip (the product that the paper's
+ * section "Limitations and future Directions" names as the next thing to fuse:
+ * Attention(Q, K, V) = softmax(Q K^T / sqrt(d_k)) V, Multi-Head Self-Attention
+ * section):
  *
  *   O[b][h][i][t] = sum_j P[b][h][i][j] * V[b][h][j][t],   P as in attnw_fused.
  *

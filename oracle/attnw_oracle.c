@@ -15,8 +15,8 @@
  *   - the max-subtracted form with m_i = max_j Z_ij   (Softmax section, Eq. 1),
  *     which has the same value and keeps exp() away from overflow;
  *   - the attention output  Attention(Q,K,V) = softmax(Q K^T / sqrt(d_k)) V
- *     (Multi-Head Self-Attention section; the paper's Conclusion names fusing
- *     this product into the kernel as the next step);
+ *     (Multi-Head Self-Attention section; the section "Limitations and future
+ *     Directions" names fusing this product into the kernel as the next step);
  *   - the scaling step on its own, scores divided by sqrt(d_k) as a separate
  *     pass over the matrix (section "Fused Matrix Multiply + Scaling +
  *     Softmax": the unfused pipeline runs multiply, scaling and softmax as

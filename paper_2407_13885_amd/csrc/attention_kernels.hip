@@ -1,6 +1,7 @@
 // Attention output  O = softmax(scale * Q K^T) V  with the attention weights kept on chip.
 //
-// The paper's Conclusion names the product with V as the next thing to fuse into its kernel
+// The paper's section "Limitations and future Directions" names the product with V as the next thing
+// to fuse into its kernel
 // (Multi-Head Self-Attention section: Attention(Q, K, V) = softmax(Q K^T / sqrt(d_k)) V).  Once the
 // weights are not written, nothing forces two sweeps over the keys: the max-subtracted softmax
 // (Softmax section, Eq. 1) is applied incrementally -- a reference exponent that follows the running

@@ -41,7 +41,10 @@ int run_qk(bool scores_only, const void* Q, const void* K, void* out, int64_t B,
         return ATTNW_ERR_SHAPE;
     const int es = elem_size(dtype);
     if (mul_overflows(in_elems, es, &in_bytes) || mul_overflows(out_elems, es, &out_bytes)) return ATTNW_ERR_SHAPE;
-    if (d < 16 || d > 256 || (d % 16) != 0) return ATTNW_ERR_UNSUPPORTED;
+    // rows of Q and K are read as 16-byte chunks: 8 bf16 or 4 fp32 elements (bf16 additionally in whole
+    // 32-byte contraction groups)
+    const int64_t d_step = dtype == ATTNW_F32 ? 4 : 16;
+    if (d < d_step || d > 256 || (d % d_step) != 0) return ATTNW_ERR_UNSUPPORTED;
     if (N > (int64_t)1 << 30) return ATTNW_ERR_UNSUPPORTED;
     // one workgroup per (head, strip of at least 64 queries), grid padded to a multiple of 8
     const int64_t strips = (N + 63) / 64;

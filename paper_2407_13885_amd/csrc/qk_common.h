@@ -59,7 +59,7 @@ __device__ __forceinline__ void dma16(const char* __restrict__ src, char* __rest
 __device__ __forceinline__ void dma16_untracked(const char* src, uint32_t lds_base)
 {
 #if defined(__HIP_DEVICE_COMPILE__)
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(src) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(src) : "memory", "m0");
 #endif
 }
 

@@ -585,6 +585,7 @@ hipError_t launch_qk(DType dt, bool scores_only, const void* Q, const void* K, v
     if (dt == DType::F32) return launch_qk_t<float>(scores_only, Q, K, out, BH, (int)N, (int)d, scale, stream, true);
     // ATTNW_FUSED_KERNEL=twopass keeps bf16 problems on the two-pass kernel above, =rounds keeps short sequences
     // off the resident kernel (tests and measurements compare the three)
+    // (read at every call: the parity tests switch it between calls; one getenv against a launch of microseconds)
     const char* force = getenv("ATTNW_FUSED_KERNEL");
     const bool twopass = force && strcmp(force, "twopass") == 0;
     const bool rounds = force && strcmp(force, "rounds") == 0;

@@ -201,7 +201,9 @@ void softmax_elem_kernel(const TI* S, TO* P, int64_t rows, int cols)
     TO* dst = P + row * cols;
     const int groups = cols / EG;
     float x[R][EG];
-    float m = kNegBig;
+    // absent elements are -inf: below every finite score, however low (a fully masked row of the lowest
+    // finite value is uniform, Eq. 1), and 2^(-inf - m) = 0
+    float m = -INFINITY;
 #pragma unroll
     for (int k = 0; k < R; ++k) {
         const int g = tid + k * TPR;
@@ -209,7 +211,7 @@ void softmax_elem_kernel(const TI* S, TO* P, int64_t rows, int cols)
             load_group<TI, EG>(src + g * EG, x[k]);
         } else {
 #pragma unroll
-            for (int i = 0; i < EG; ++i) x[k][i] = kNegBig;
+            for (int i = 0; i < EG; ++i) x[k][i] = -INFINITY;
         }
 #pragma unroll
         for (int i = 0; i < EG; ++i) m = fmaxf(m, x[k][i]);
@@ -220,7 +222,7 @@ void softmax_elem_kernel(const TI* S, TO* P, int64_t rows, int cols)
     for (int k = 0; k < R; ++k) {
 #pragma unroll
         for (int i = 0; i < EG; ++i) {
-            x[k][i] = fast_exp2((x[k][i] - m) * kLog2e);     // absent elements: 2^(-huge) = 0
+            x[k][i] = fast_exp2((x[k][i] - m) * kLog2e);     // absent elements: 2^(-inf) = 0
             l += x[k][i];
         }
     }
@@ -278,7 +280,9 @@ void softmax_long_kernel(const TI* S, TO* P, int64_t rows, int64_t cols, int chu
     const int64_t g0 = piece_begin(chunk), g1 = piece_begin(chunk + 1);
 
     // ---- statistics: per-thread running maximum m and l = sum 2^((x - m) log2 e) -------------------------
-    float m = kNegBig, l = 0.0f;
+    // "nothing seen yet" is (-inf, 0): any finite score, however low, replaces it (2^(-inf) = 0 clears the
+    // empty sum); two empty pairs are merged with factor 1, never through -inf - (-inf)
+    float m = -INFINITY, l = 0.0f;
     auto fold = [&](const float* x, int n) __attribute__((always_inline)) {
         float gm = x[0];
 #pragma unroll
@@ -327,7 +331,9 @@ void softmax_long_kernel(const TI* S, TO* P, int64_t rows, int64_t cols, int chu
     for (int off = 32; off > 0; off >>= 1) {
         const float mo = __shfl_xor(m, off, 64), lo = __shfl_xor(l, off, 64);
         const float mn = fmaxf(m, mo);
-        l = l * fast_exp2((m - mn) * kLog2e) + lo * fast_exp2((mo - mn) * kLog2e);
+        const float fa = m == mn ? 1.0f : fast_exp2((m - mn) * kLog2e);
+        const float fb = mo == mn ? 1.0f : fast_exp2((mo - mn) * kLog2e);
+        l = l * fa + lo * fb;
         m = mn;
     }
     __shared__ float sm[WAVES], sl[WAVES];

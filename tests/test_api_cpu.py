@@ -64,6 +64,8 @@ def test_fused_validation_order(lib):
     assert f(QA, KA, PA, 1 << 20, 1 << 20, 1 << 20, 64, 0.125, BF16, None) == E_SHAPE
     for d in (0, 8, 24, 100, 272, 512):
         assert f(QA, KA, PA, 1, 1, 128, d, 0.125, BF16, None) == E_UNSUP, d
+    for d in (0, 2, 6, 30, 260, 512):            # fp32 rows are whole 16-byte chunks: multiples of 4
+        assert f(QA, KA, PA, 1, 1, 128, d, 0.125, F32, None) == E_UNSUP, d
     assert f(QA, KA, PA, 1, 1, (1 << 30) + 1, 64, 0.125, BF16, None) == E_UNSUP
     assert f(QA + 2, KA, PA, 1, 1, 128, 64, 0.125, BF16, None) == E_ALIGN
     assert f(QA, KA + 8, PA, 1, 1, 128, 64, 0.125, BF16, None) == E_ALIGN

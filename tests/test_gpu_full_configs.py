@@ -1,9 +1,8 @@
 """GPU parity at the full benchmark sizes, in the launch configuration bench.py times.
 
-c2 and c3 are compared with the oracle on every element.  c4 and c5 are compared on
-sampled query rows (first / last rows of strips, strip interiors, seeded random rows of
-every head), which the oracle computes one by one, and on a property that holds at any
-size and needs no oracle: every row of P sums to 1."""
+Every configuration is compared with the oracle on every element (c4 and c5 in blocks of
+512 query rows, which the oracle computes on all host cores), and on a property that
+holds at any size and needs no oracle: every row of P sums to 1."""
 import numpy as np
 import pytest
 import torch
@@ -53,18 +52,21 @@ def test_c3_full_fused_bf16():
 
 
 @pytest.mark.parametrize("name", ["c4", "c5"])
-def test_large_fused_sampled_rows_and_row_sums(name):
+def test_large_fused_every_element_and_row_sums(name):
+    """Every element of c4 (2.7e8) and c5 (2.1e9) against the oracle, 512 query rows at a time.  On a 16-thread
+    host the oracle takes about 2 s for c4 and 15 s for c5; with the comparison the test runs about 10 s / 80 s."""
+    import sys
     x = wl.CONFIGS[name]()
     P = gu.run_fused(x, guard=8192)
     _row_sums_ok(P, gu.ROWSUM_BF16)
-    assert bool(torch.isfinite(P.view(-1)[:: 4099].float()).all().item())
+    step = 512
     for b in range(x.B):
         for h in range(x.H):
-            rows = _sample_rows(x.N, seed=1000 * b + h)
-            got = gu.to_f64(P[b, h][rows])
-            ref = np.concatenate([oracle.attention_weights(x.Q[b, h], x.K[b, h], "bf16", x.scale, rows=(r, r + 1))
-                                  for r in rows])
-            gu.check_weights(got, ref, "bf16", f"{name} head ({b},{h}) sampled rows")
+            for r0 in range(0, x.N, step):
+                r1 = min(r0 + step, x.N)
+                ref = oracle.attention_weights(x.Q[b, h], x.K[b, h], "bf16", x.scale, rows=(r0, r1))
+                gu.check_weights(gu.to_f64(P[b, h, r0:r1]), ref, "bf16", f"{name} head ({b},{h}) rows {r0}..{r1}")
+            print(f"  {name} head ({b},{h}) ok", file=sys.stderr, flush=True)
 
 
 def test_c4_unfused_pair_full_size():

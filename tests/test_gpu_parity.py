@@ -143,7 +143,7 @@ def test_fused_ragged_n(N, dtype):
     gu.check_weights(gu.to_f64(P), _oracle_heads(x), dtype, f"fused {dtype} N={N}")
 
 
-@pytest.mark.parametrize("d", [16, 32, 48, 64, 80, 128, 192, 256])
+@pytest.mark.parametrize("d", [4, 8, 12, 16, 20, 32, 36, 48, 64, 68, 80, 100, 128, 192, 252, 256])
 def test_fused_fp32_all_d(d):
     x = wl.fused_inputs("t", "f32", 1, 1, 160, d, seed=300 + d)
     P = gu.run_fused(x, guard=4096)
@@ -245,6 +245,27 @@ def test_softmax_in_place(dtype, cols):
     P = gu.run_softmax(S, 21, cols, dtype, inplace=True)
     assert P.data_ptr() == S.data_ptr()
     gu.check_weights(gu.to_f64(P), oracle.softmax(s.S, dtype), dtype, f"in-place {dtype} cols={cols}")
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("cols", [7, 100, 1001, 2048, 2049, 70000, 300001])
+def test_softmax_rows_of_the_lowest_finite_value(dtype, cols):
+    """A fully masked row (every score the lowest finite value of the type) is finite input: Eq. 1 gives the
+    uniform 1/cols, whichever kernel the row length selects.  Rows that hold one ordinary score among
+    them put all the weight on it."""
+    rows = 5
+    s = wl.softmax_inputs("t", dtype, rows, cols, seed=2100 + cols, sigma=2.0)
+    lowest = np.float32(-3.3895314e38)          # the lowest finite bf16 value, also an fp32 value
+    S = s.S.copy()
+    low = lowest if dtype == "f32" else np.uint16(0xff7f)
+    S[0, :] = low
+    S[2, :] = low
+    S[3, :] = low
+    S[3, cols // 2] = np.float32(1.5) if dtype == "f32" else np.uint16(0x3fc0)
+    P = gu.run_softmax(gu.to_dev(S, dtype), rows, cols, dtype, guard=4096)
+    got = gu.to_f64(P)
+    gu.check_weights(got, oracle.softmax(S, dtype), dtype, f"masked rows {dtype} cols={cols}")
+    assert np.allclose(got[0], 1.0 / cols, rtol=4e-3) and got[3, cols // 2] == 1.0
 
 
 def test_softmax_large_offsets_fp32():
