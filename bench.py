@@ -11,16 +11,21 @@ dedicated softmax on c2, the fused kernel on c3 and c5, the unfused pair
 (score GEMM, then softmax) and the three-kernel pipeline (multiply, scaling,
 softmax) on c3..c5 for the fused-vs-unfused ratios, and the attention output.
 
-Timing: W untimed calls, then exactly K calls bracketed by a device
+Timing: every timed section starts with an untimed pre-heat of about 0.4 s of
+the section's own call (the shader clock starts low on an idle GPU and takes a
+few hundred milliseconds of load to settle; a 5 + 20 call measurement of a
+0.2 ms kernel would sit entirely inside that ramp), reported as ``preheat_ms``;
+then W untimed calls, then exactly K calls bracketed by a device
 synchronisation on both sides (wall clock -> ``ms_per_step`` and ``value``) and
 by HIP events recorded on the stream the kernels are launched on (-> the
-average launch duration used for the roofline).  Without --steps / --warmup, W
-and K are sized per timed section from a three-call pilot so that the warm-up
-lasts about 0.4 s and the timed region about 0.3 s: the shader clock starts
-low on an idle GPU and takes a few hundred milliseconds of load to settle, and
-a 5 + 20 call measurement of a 0.2 ms kernel sits entirely inside that ramp.  Working sets smaller than the
-256 MB last-level cache are rotated through distinct buffers (> 1 GiB in total)
-so that no call finds its data on chip.
+average launch duration used for the roofline).  ``steps`` and ``warmup`` in
+the JSON line are K and W as given; without the flags W = 5 and K is sized from
+a three-call pilot so that the timed region lasts about 0.3 s.  Working sets
+smaller than the 256 MB last-level cache are rotated through distinct buffers
+(> 1 GiB in total) so that no call finds its data on chip.  Right after the
+headline section has been timed its call is launched back to back for another
+1.5 s while a child process samples board power and shader clock
+(``amd-smi metric -p -c``); the readings go into the line as ``power``.
 
 The CPU oracle is timed in the same run on the host cores (``cpu_baseline``):
 a reported baseline, not the target.
@@ -52,29 +57,98 @@ def _dev(a, dtype):
     return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda().view(torch.bfloat16)
 
 
-WARM_MS = 400.0   # default warm-up per timed section: the shader clock needs this long under load to settle
+WARM_MS = 400.0   # untimed pre-heat per timed section: the shader clock needs this long under load to settle
 TIMED_MS = 300.0  # default length of a timed section
+LAST_PREHEAT_MS = 0.0   # wall time of the most recent section's pre-heat (reported with the headline)
+
+
+class PowerSampler:
+    """Board power and shader clock while a section runs: a thread that keeps calling ``amd-smi metric -p -c``
+    (a child process per sample) and keeps the readings.  Absent tool or unparsable output: no samples."""
+
+    def __init__(self, period_s=0.15):
+        import threading
+        self.period_s = period_s
+        self.samples = []
+        self._stop = threading.Event()
+        self._thread = threading.Thread(target=self._run, daemon=True)
+
+    def _run(self):
+        import re
+        import subprocess
+        while not self._stop.is_set():
+            try:
+                out = subprocess.run(["amd-smi", "metric", "-p", "-c"], capture_output=True, text=True, timeout=5).stdout
+            except (OSError, subprocess.SubprocessError):
+                return
+            block = out.split("GPU: 1")[0]
+            m = re.search(r"SOCKET_POWER:\s*(\d+)", block)
+            clks = [int(c) for c in re.findall(r"GFX_\d+:\s*\n\s*CLK:\s*(\d+)", block)]
+            if m:
+                self.samples.append((int(m.group(1)), clks))
+            self._stop.wait(self.period_s)
+
+    def start(self):
+        self._thread.start()
+        return self
+
+    def stop(self):
+        self._stop.set()
+        self._thread.join(timeout=10)
+        if not self.samples:
+            return None
+        top = max(self.samples, key=lambda s: s[0])
+        clocks = [c for c in top[1] if c > 0]
+        return {"socket_power_W": top[0], "gfx_clock_MHz_min": min(clocks) if clocks else None,
+                "gfx_clock_MHz_max": max(clocks) if clocks else None, "samples": len(self.samples),
+                "source": "amd-smi metric -p -c while the headline call is launched back to back for 1.5 s right "
+                          "after its timed region; the sample with the highest socket power"}
+
+
+POWER_WINDOW_MS = 1500.0
+
+
+def _power_window(call, n_sets):
+    """After a section has been timed: keep launching its call for POWER_WINDOW_MS (untimed) while board power and
+    shader clock are sampled -- the state the timed calls ran in, read without disturbing them."""
+    import torch
+    sampler = PowerSampler().start()
+    t0 = time.perf_counter()
+    while (time.perf_counter() - t0) * 1e3 < POWER_WINDOW_MS:
+        for i in range(50):
+            call(i % n_sets)
+        torch.cuda.synchronize()
+    return sampler.stop()
 
 
 def _time_calls(call, n_sets, steps, warmup):
-    """call(i) launches one step on buffer set i % n_sets.  ``steps`` / ``warmup`` None: sized from a
-    short pilot run so that the warm-up covers WARM_MS and the timed region TIMED_MS.
-    Returns (wall ms/step, event ms/step, steps, warmup)."""
+    """call(i) launches one step on buffer set i % n_sets.  A pre-heat of about WARM_MS of calls (sized from a
+    three-call pilot) comes first, whatever ``steps`` / ``warmup`` say; ``warmup`` None: 5 calls; ``steps``
+    None: as many as fill TIMED_MS.  Returns (wall ms/step, event ms/step, steps, warmup)."""
     import torch
+    global LAST_PREHEAT_MS
     stream = torch.cuda.current_stream()
-    if steps is None or warmup is None:
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        call(0)
-        e0.record(stream)
-        for i in range(3):
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    call(0)
+    e0.record(stream)
+    for i in range(3):
+        call(i % n_sets)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    pilot = max(e0.elapsed_time(e1) / 3, 1e-3)
+    t0 = time.perf_counter()
+    batch = min(max(int(50.0 / pilot), 1), 5000)        # about 50 ms of calls between looks at the clock
+    while True:
+        for i in range(batch):
             call(i % n_sets)
-        e1.record(stream)
         torch.cuda.synchronize()
-        pilot = max(e0.elapsed_time(e1) / 3, 1e-3)
-        if warmup is None:
-            warmup = min(max(int(WARM_MS / pilot), 5), 50000)
-        if steps is None:
-            steps = min(max(int(TIMED_MS / pilot), 20), 50000)
+        LAST_PREHEAT_MS = (time.perf_counter() - t0) * 1e3
+        if LAST_PREHEAT_MS >= WARM_MS:
+            break
+    if warmup is None:
+        warmup = 5
+    if steps is None:
+        steps = min(max(int(TIMED_MS / pilot), 20), 50000)
     for i in range(warmup):
         call(i % n_sets)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -101,13 +175,14 @@ def _record(name, what, elements, alg_bytes, timing, n_sets):
     return {
         "workload": name, "call": what, "elements": elements, "algorithmic_bytes": alg_bytes,
         "steps": steps, "warmup": warmup,
+        "preheat_ms": round(LAST_PREHEAT_MS, 1),
         "ms_per_step": round(wall_ms, 5), "kernel_ms": round(ev_ms, 5),
         "elements_per_s": elements / (wall_ms * 1e-3),
         "hbm_GBps": round(gbs, 1), "hbm_frac_of_peak": round(gbs / HBM_PEAK_GBS, 4), "buffer_sets": n_sets,
     }
 
 
-def bench_softmax(cfg, steps, warmup):
+def bench_softmax(cfg, steps, warmup, sample_power=False):
     import torch
     import paper_2407_13885_amd as attnw
     x = cfg()
@@ -122,8 +197,11 @@ def bench_softmax(cfg, steps, warmup):
         attnw.attnw_softmax(S[i], P[i], x.rows, x.cols, dt, stream)
 
     timing = _time_calls(call, n_sets, steps, warmup)
+    power = _power_window(call, n_sets) if sample_power else None
     rs = float((P[0].float().sum(-1) - 1.0).abs().max().item())
     rec = _record(x.name, "attnw_softmax", x.elements, x.algorithmic_bytes, timing, n_sets)
+    if sample_power:
+        rec["power"] = power
     rec["max_row_sum_error"] = rs
     rec["shape"] = {"rows": x.rows, "cols": x.cols, "dtype": x.dtype}
     return rec, x
@@ -132,7 +210,7 @@ def bench_softmax(cfg, steps, warmup):
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16, published
 
 
-def bench_fused(cfg, steps, warmup, with_unfused=True, with_attention=True):
+def bench_fused(cfg, steps, warmup, with_unfused=True, with_attention=True, sample_power=False):
     import torch
     import paper_2407_13885_amd as attnw
     x = cfg()
@@ -150,8 +228,11 @@ def bench_fused(cfg, steps, warmup, with_unfused=True, with_attention=True):
         attnw.attnw_fused(Q, K, P[i], x.B, x.H, x.N, x.d, scale, dt, stream)
 
     timing = _time_calls(call, n_sets, steps, warmup)
+    power = _power_window(call, n_sets) if sample_power else None
     ev = timing[1]
     rec = _record(x.name, "attnw_fused", x.elements, x.algorithmic_bytes, timing, n_sets)
+    if sample_power:
+        rec["power"] = power
     rec["shape"] = {"B": x.B, "H": x.H, "N": x.N, "d": x.d, "dtype": x.dtype}
     rec["mfma_TFLOPs_two_pass"] = round(2 * 2.0 * x.elements * x.d / (ev * 1e-3) * 1e-12, 1)
     # row sums of every row (a property that needs no oracle)
@@ -405,11 +486,12 @@ def main() -> int:
     for name in todo:
         print(f"[bench] {name} ...", file=sys.stderr, flush=True)
         if name == "c2":
-            results[name], inputs[name] = bench_softmax(wl.c2, args.steps, args.warmup)
+            results[name], inputs[name] = bench_softmax(wl.c2, args.steps, args.warmup, sample_power=name == args.workload)
         else:
             results[name], inputs[name] = bench_fused(wl.CONFIGS[name], args.steps, args.warmup,
                                                       with_unfused=not args.no_unfused,
-                                                      with_attention=not args.no_attention)
+                                                      with_attention=not args.no_attention,
+                                                      sample_power=name == args.workload)
         if name != args.workload:
             inputs.pop(name)
 
@@ -425,7 +507,7 @@ def main() -> int:
         "metric": METRIC,
         "value": head["elements_per_s"],
         "unit": "elements/s",
-        "n_gpus": 1, "steps": head["steps"], "warmup": head["warmup"],
+        "n_gpus": 1, "steps": head["steps"], "warmup": head["warmup"], "preheat_ms": head["preheat_ms"],
         "ms_per_step": head["ms_per_step"],
         "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None,
@@ -437,9 +519,11 @@ def main() -> int:
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": head["hbm_GBps"], "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": head["hbm_frac_of_peak"],
                      "traffic": measured_traffic(args.workload, head["call"]),
-                     # what is observed to bind on this board (power and clock readings under profiles/)
-                     "observed_limit": ("board power cap (1400 W): shader clock throttled to 1.7-1.9 GHz"
-                                        if args.workload in ("c4", "c5") else None)},
+                     # quoted, not measured by this run: the counter summary committed with this build
+                     "traffic_source": "profiles/hbm_traffic.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this build)",
+                     "kernel_source": "the library's dispatch for this shape (kernel names as in profiles/)"},
+        # board power and shader clock read while the headline call ran (None: amd-smi absent or silent)
+        "power": head.get("power"),
         "cpu_baseline": cpu,
         "fused_vs_unfused_speedup": {k: v.get("fused_vs_unfused_speedup") for k, v in results.items()
                                      if "fused_vs_unfused_speedup" in v},

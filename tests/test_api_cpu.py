@@ -89,7 +89,7 @@ def test_gemm_scores_shares_the_rules(lib):
     g = lib.attnw_gemm_scores
     assert g(QA, KA, PA, 1, 1, 128, 64, 0.125, 2, None) == E_DTYPE
     assert g(QA, KA, None, 1, 1, 128, 64, 0.125, F32, None) == E_NULL
-    assert g(QA, KA, PA, 1, 1, 128, 20, 0.125, F32, None) == E_UNSUP
+    assert g(QA, KA, PA, 1, 1, 128, 22, 0.125, F32, None) == E_UNSUP
     assert g(QA, KA, QA, 1, 1, 128, 64, 0.125, F32, None) == E_ALIAS
 
 
