@@ -32,6 +32,13 @@ bool qk_resident_supported(int64_t BH, int64_t N, int64_t d);
 hipError_t launch_qk_resident(const void* Q, const void* K, void* out, int64_t BH, int64_t N, float scale,
                               hipStream_t stream);
 
+// Fused attention weights, bf16, d = 64 or 128, N a multiple of 512 from 1024 to 16384: the scores of a strip stay
+// in the registers of the N / 512 workgroups that share its rows (one sweep over the keys; the workgroups exchange
+// their row statistics through tables parked in P).  Two launches: table slots zeroed, then the kernel.
+bool qk_gang_supported(int64_t BH, int64_t N, int64_t d);
+hipError_t launch_qk_gang(const void* Q, const void* K, void* out, int64_t BH, int64_t N, int64_t d, float scale,
+                          hipStream_t stream);
+
 // Y = scale * X over count elements, rounded once to the storage type; X == Y allowed.
 hipError_t launch_scale(DType dt, const void* X, void* Y, int64_t count, float scale, hipStream_t stream);
 

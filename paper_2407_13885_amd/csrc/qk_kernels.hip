@@ -589,6 +589,8 @@ hipError_t launch_qk(DType dt, bool scores_only, const void* Q, const void* K, v
     const char* force = getenv("ATTNW_FUSED_KERNEL");
     const bool twopass = force && strcmp(force, "twopass") == 0;
     const bool rounds = force && strcmp(force, "rounds") == 0;
+    const bool gang = force && strcmp(force, "gang") == 0;
+    if (gang && !scores_only && qk_gang_supported(BH, N, d)) return launch_qk_gang(Q, K, out, BH, N, d, scale, stream);
     if (!twopass && !(!rounds && prefers_key_split(BH, N, d))) {
         if (!scores_only && !rounds && qk_resident_supported(BH, N, d))
             return launch_qk_resident(Q, K, out, BH, N, scale, stream);

@@ -1,0 +1,64 @@
+"""GPU parity of the kernel that keeps the scores of a strip resident across compute units (one sweep over
+the keys; the workgroups that share a row exchange their row statistics through tables parked in P)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2407_13885_amd import workloads as wl
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _gpu():
+    gu.require_gpu()
+
+
+@pytest.fixture(autouse=True)
+def _force(monkeypatch):
+    monkeypatch.setenv("ATTNW_FUSED_KERNEL", "gang")
+
+
+def _check_all(x, P, what):
+    got = gu.to_f64(P)
+    for b in range(x.B):
+        for h in range(x.H):
+            ref = oracle.attention_weights(x.Q[b, h], x.K[b, h], "bf16", x.scale)
+            gu.check_weights(got[b, h], ref, "bf16", f"{what} head ({b},{h})")
+
+
+# gangs of 2, 3, 5, 8, 16 workgroups of four waves (key ranges of 256, N <= 4096) and of 10, 16 and 32 workgroups of
+# eight waves (key ranges of 512, d = 64 beyond 4096); lists of one strip (fewer strips than gangs), lists that cross
+# heads, lists of a whole head; both head sizes; sharp and flat rows; a negative scale
+@pytest.mark.parametrize("B,H,N,d,scale", [(1, 1, 512, 64, None), (1, 3, 768, 128, None), (3, 3, 1024, 64, -0.2),
+                                           (1, 2, 1280, 128, None), (1, 5, 2048, 128, None), (2, 3, 2048, 64, None),
+                                           (1, 1, 4096, 128, None), (1, 3, 4096, 64, -0.11), (1, 40, 1024, 128, None),
+                                           (1, 2, 5120, 64, None), (1, 1, 8192, 64, None), (1, 1, 16384, 64, None)])
+def test_gang_kernel_against_the_oracle(B, H, N, d, scale):
+    x = wl.fused_inputs("t", "bf16", B, H, N, d, seed=7100 + H + N + d, scale=scale, row_factor=(0.5, 3.0))
+    P = gu.run_fused(x, guard=8192)
+    _check_all(x, P, f"gang kernel {B}x{H}x{N}x{d}")
+
+
+def test_gang_kernel_is_deterministic_and_ignores_what_p_held():
+    """The exchange tables are parked in P: whatever P held before the call (all ones, NaN patterns, the
+    previous result) must not matter, and two calls give the same bits."""
+    x = wl.fused_inputs("t", "bf16", 1, 4, 2048, 128, seed=7200, row_factor=(0.5, 3.0))
+    import paper_2407_13885_amd as attnw
+    Q, K = gu.to_dev(x.Q, "bf16"), gu.to_dev(x.K, "bf16")
+    outs = []
+    for fill in (0x3f80, 0xffff, 0x7fc0, None):
+        P = torch.empty((x.B, x.H, x.N, x.N), dtype=torch.bfloat16, device="cuda")
+        if fill is None:
+            P.copy_(outs[0])
+        else:
+            P.view(torch.int16).fill_(fill - 0x10000 if fill >= 0x8000 else fill)
+        attnw.attnw_fused(Q, K, P, x.B, x.H, x.N, x.d, float(x.scale), attnw.ATTNW_BF16)
+        torch.cuda.synchronize()
+        outs.append(P)
+    for o in outs[1:]:
+        assert torch.equal(o.view(torch.int16), outs[0].view(torch.int16))
+    _check_all(x, outs[0], "gang kernel, prefilled P")
