@@ -11,12 +11,15 @@
 // of a head, and the G = N / KR workgroups that share the rows of a strip -- a "gang" -- exchange
 // their (maximum, sum) pairs through device memory.
 //
-// NOT the dispatch default: measured on one MI355X it is no faster than the kernels that sweep the
-// keys twice (B1 H16 N4096 d128: 177-196 us against 177-188 us; B1 H8 N16384 d64: 1250-1420 us against
-// 990 us).  The second sweep it saves is matrix-core work, which already hides behind the vector ALU,
-// and the vector ALU gains nothing: the exponential that is saved comes back as the multiplication
-// by the normaliser, and the exchange costs instructions of its own.  It is kept, behind
-// ATTNW_FUSED_KERNEL=gang, as the measured answer to "what does the paper's own structure do here".
+// Where it is used: problems of one to a few heads, with less than one 128-query strip per compute
+// unit -- the sizes the paper itself measures are single heads.  The kernels that sweep the keys twice
+// have a workgroup per strip and leave most of the chip idle there; this one puts every compute unit
+// on the keys of the few strips (one head, d = 128: N = 1024 20.8 -> 14.9 us, 4096 36.5 -> 26.1 us).
+// On large problems it is NOT faster than the two-sweep kernels, measured on one MI355X: B1 H16 N4096
+// d128 177-196 us against 177-188 us; B1 H8 N16384 d64 1250-1420 us against 990 us.  The second sweep
+// it saves is matrix-core work, which already hides behind the vector ALU, and the vector ALU gains
+// nothing: the exponential that is saved comes back as the multiplication by the normaliser, and the
+// exchange costs instructions of its own.  ATTNW_FUSED_KERNEL=gang forces it wherever it applies.
 //
 // The only memory a call may write is P, so the exchange tables live in P itself: the pair table of
 // strip s of a workgroup is parked in the part of P that the SAME workgroup fills with the weights
@@ -28,10 +31,12 @@
 // a sum of exponentials against the own maximum is at least 1).
 //
 // All workgroups of a gang must be running at the same time: the grid is exactly as many workgroups
-// as the compute units hold at once (LDS and registers leave room for no more), gangs are consecutive
-// blocks of one XCD, and every wait is bounded -- a gang member that never shows up (another kernel
-// holding its compute unit, say) turns the rows that wait for it into NaN instead of hanging the
-// device.  Another reason why this is not a default path.
+// as the compute units hold at once (LDS and registers leave room for no more) and gangs are
+// consecutive blocks of one XCD, so that on a device that hands out workgroups in block order a gang
+// is complete as soon as its last member has a place, whatever else runs beside the kernel (complete
+// gangs finish on their own and make room).  Every wait is bounded all the same: a gang member that
+// does not show up within some tenths of a second turns the rows that wait for it into NaN instead
+// of hanging the device.
 //
 // Per workgroup (wave w owns keys 64 w .. 64 w + 63 of the workgroup's KR, as two 32-key pieces; all
 // waves work on the same 32 queries), iteration i of its strip list:

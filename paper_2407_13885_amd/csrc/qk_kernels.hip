@@ -577,6 +577,19 @@ bool prefers_key_split(int64_t BH, int64_t N, int64_t d)
     return 4 * strips <= cus || (2 * strips <= cus && N >= 8192);
 }
 
+// Problems with less than one 128-query strip per compute unit (one to a few heads: the sizes the paper itself
+// measures are single heads) leave the persistent two-sweep kernels without work for most of the chip, and the
+// key split above pays for it with two launches.  The kernel that spreads the keys of a strip over a gang of
+// workgroups keeps every compute unit busy on them.  Measured, one head, default -> gang: d = 128, N = 1024
+// 20.8 -> 14.9 us, 2048 25.4 -> 17.1, 4096 36.5 -> 26.1 (two heads 70 -> 37.5, four 75 -> 58); d = 64, N = 2048
+// 18.3 -> 11.2, 4096 32.5 -> 19.0, 8192 60 -> 44; from one strip per compute unit on, and at N = 16384, the
+// two-sweep kernels are as fast or faster.
+bool prefers_gang(int64_t BH, int64_t N, int64_t d)
+{
+    if (N < 1024 || N > 8192) return false;
+    return BH * (N / 128) < (int64_t)compute_units();
+}
+
 }  // namespace
 
 hipError_t launch_qk(DType dt, bool scores_only, const void* Q, const void* K, void* out,
@@ -590,7 +603,8 @@ hipError_t launch_qk(DType dt, bool scores_only, const void* Q, const void* K, v
     const bool twopass = force && strcmp(force, "twopass") == 0;
     const bool rounds = force && strcmp(force, "rounds") == 0;
     const bool gang = force && strcmp(force, "gang") == 0;
-    if (gang && !scores_only && qk_gang_supported(BH, N, d)) return launch_qk_gang(Q, K, out, BH, N, d, scale, stream);
+    if (!scores_only && qk_gang_supported(BH, N, d) && (gang || (!force && prefers_gang(BH, N, d))))
+        return launch_qk_gang(Q, K, out, BH, N, d, scale, stream);
     if (!twopass && !(!rounds && prefers_key_split(BH, N, d))) {
         if (!scores_only && !rounds && qk_resident_supported(BH, N, d))
             return launch_qk_resident(Q, K, out, BH, N, scale, stream);
