@@ -361,7 +361,7 @@ SHAPES_SOFTMAX = [(1024, 1024), (2048, 2048), (4096, 4096), (8192, 8192), (16384
                   (96, 524288), (16, 4194304), (100000, 512), (100000, 100), (1000000, 48)]
 # (first five: one head of n x 128, the sizes of the paper's Table I)
 SHAPES_QK = [("bf16", 1, 1, 1024, 128), ("bf16", 1, 1, 2048, 128), ("bf16", 1, 1, 4096, 128), ("bf16", 1, 1, 8192, 128),
-             ("bf16", 1, 1, 16384, 128), ("bf16", 1, 16, 4096, 128), ("bf16", 1, 16, 4096, 64), ("bf16", 1, 16, 4096, 96), ("bf16", 1, 16, 4096, 256),
+             ("bf16", 1, 1, 16384, 128), ("bf16", 1, 2, 4096, 128), ("bf16", 1, 4, 4096, 128), ("bf16", 1, 8, 4096, 128), ("bf16", 1, 16, 4096, 128), ("bf16", 1, 24, 4096, 128), ("bf16", 1, 32, 4096, 128), ("bf16", 1, 16, 4096, 64), ("bf16", 1, 16, 4096, 96), ("bf16", 1, 16, 4096, 256),
              ("bf16", 1, 16, 4000, 128), ("bf16", 1, 16, 4104, 128), ("bf16", 1, 16, 4097, 128), ("bf16", 1, 16, 3968, 64),
              ("bf16", 8, 16, 640, 64), ("bf16", 64, 16, 128, 64), ("bf16", 64, 16, 197, 64), ("f32", 1, 16, 2048, 64),
              ("f32", 1, 16, 4000, 64)]
@@ -442,6 +442,9 @@ def main() -> int:
                     help="configuration reported at the top level of the JSON line")
     ap.add_argument("--only", action="store_true", help="measure the headline workload only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-power", action="store_true",
+                    help="do not sample board power and shader clock (the sampler starts child processes, which a "
+                         "profiler that preloads itself into every process does not allow)")
     ap.add_argument("--no-unfused", action="store_true", help="skip the unfused pair (score GEMM, then softmax)")
     ap.add_argument("--no-attention", action="store_true", help="skip attnw_attention (O = P V with P kept on chip)")
     ap.add_argument("--shapes", action="store_true",
@@ -480,18 +483,20 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
+    # (rocprofv3 preloads a library into every process: no child processes under it)
+    sample = not args.no_power and "rocprof" not in os.environ.get("LD_PRELOAD", "")
     order = ["c2", "c3", "c4", "c5"]
     todo = [args.workload] if args.only else order
     results, inputs = {}, {}
     for name in todo:
         print(f"[bench] {name} ...", file=sys.stderr, flush=True)
         if name == "c2":
-            results[name], inputs[name] = bench_softmax(wl.c2, args.steps, args.warmup, sample_power=name == args.workload)
+            results[name], inputs[name] = bench_softmax(wl.c2, args.steps, args.warmup, sample_power=sample and name == args.workload)
         else:
             results[name], inputs[name] = bench_fused(wl.CONFIGS[name], args.steps, args.warmup,
                                                       with_unfused=not args.no_unfused,
                                                       with_attention=not args.no_attention,
-                                                      sample_power=name == args.workload)
+                                                      sample_power=sample and name == args.workload)
         if name != args.workload:
             inputs.pop(name)
 
