@@ -157,8 +157,9 @@ int attnw_scale(const void *X, void *Y, int64_t count, float scale,
  * P is never written to device memory: one sweep over the keys with a running
  * row maximum and sum (Eq. 1 applied incrementally); the weights are rounded to
  * bf16 before they multiply V on the matrix cores, the output once more at the store.
- * Supported so far: dtype ATTNW_BF16, d = 32, 64 or 128, any N >= 1 (multiples of
- * 256 take the fast path; other lengths clamp and mask the rows past the end).
+ * Supported so far: dtype ATTNW_BF16, d a multiple of 16 up to 128, any N >= 1
+ * (d = 32, 64, 128 with N a multiple of 256 take the fast path; other head sizes
+ * are padded on chip, other lengths clamp and mask the rows past the end).
  * Anything else: ATTNW_ERR_UNSUPPORTED.  O must not overlap Q, K or V.
  * Validation order as for attnw_fused.
  */

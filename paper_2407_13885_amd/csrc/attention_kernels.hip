@@ -69,11 +69,15 @@ struct AttnCfg {
 
 // TAIL: N is not a whole number of tiles / strips.  Rows past the end are read as row N-1 (every load
 // stays inside the arrays), their weights are forced to 0 and their queries are not stored.
-template <int DB, int QB, bool TAIL>
+// PAD:  rows of Q, K, V and O are `rb` < DB bytes long (head sizes that are not 32, 64 or 128); on chip they are
+// padded to DB: Q fragments and V columns past the end are zeros, K chunks past the end hold a copy of the row's
+// first chunk (finite, and it meets the zero Q fragments), output columns past the end are not stored.
+template <int DB, int QB, bool TAIL, bool PAD = false>
 __global__ __launch_bounds__(512)
 void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
-                      uint16_t* __restrict__ O, int N, float c, uint32_t sign_flip, uint32_t strips, uint32_t total)
+                      uint16_t* __restrict__ O, int N, int rb_arg, float c, uint32_t sign_flip, uint32_t strips, uint32_t total)
 {
+    const int rb = PAD ? rb_arg : DB;             // bytes of a row in memory
     using C = AttnCfg<DB, QB>;
     constexpr int NW = C::NW, QW = C::QW, BM = C::BM, BN = C::BN, G = C::G, CPR = C::CPR, DVB = C::DVB;
     constexpr int K_TILE_BYTES = C::K_TILE_BYTES, K_LOADS = C::K_LOADS, V_LOADS = C::V_LOADS;
@@ -96,10 +100,10 @@ void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
     const int l32 = lane & 31;
     const int half = lane >> 5;
 
-    const char* Qh = reinterpret_cast<const char*>(Q) + (int64_t)bh * N * DB;
-    const char* Kh = reinterpret_cast<const char*>(K) + (int64_t)bh * N * DB;
-    const char* Vh = reinterpret_cast<const char*>(V) + (int64_t)bh * N * DB;
-    char* Oh = reinterpret_cast<char*>(O) + (int64_t)bh * N * DB;
+    const char* Qh = reinterpret_cast<const char*>(Q) + (int64_t)bh * N * rb;
+    const char* Kh = reinterpret_cast<const char*>(K) + (int64_t)bh * N * rb;
+    const char* Vh = reinterpret_cast<const char*>(V) + (int64_t)bh * N * rb;
+    char* Oh = reinterpret_cast<char*>(O) + (int64_t)bh * N * rb;
     const int q0 = strip * BM + wave * QW;
 
     auto row_in = [&](int r) __attribute__((always_inline)) { return TAIL ? min(r, N - 1) : r; };
@@ -109,8 +113,12 @@ void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-        for (int g = 0; g < G; ++g)
-            qf[qb][g] = *reinterpret_cast<const u32x4*>(Qh + (int64_t)row_in(q0 + qb * 32 + l32) * DB + (2 * g + half) * 16) ^ sign_flip;
+        for (int g = 0; g < G; ++g) {
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (!PAD || (2 * g + half) * 16 < rb)
+                v = *reinterpret_cast<const u32x4*>(Qh + (int64_t)row_in(q0 + qb * 32 + l32) * rb + (2 * g + half) * 16) ^ sign_flip;
+            qf[qb][g] = v;
+        }
 
     // ---- per-lane constants ----------------------------------------------------------------------------
     // K tile transfer j of this lane: key within the tile (recomputed where a clamp needs it), byte offset in the tile
@@ -119,7 +127,9 @@ void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
 #pragma unroll
     for (int j = 0; j < K_LOADS; ++j) {
         const int s = (wave + NW * j) * 64 + lane;
-        k_off[j] = k_key(j) * DB + ((s % CPR) ^ ((k_key(j) / C::RPL) & C::SWZ_MASK)) * 16;
+        int ch = (s % CPR) ^ ((k_key(j) / C::RPL) & C::SWZ_MASK);
+        if (PAD && ch * 16 >= rb) ch = 0;         // a padding chunk: any finite data of the row
+        k_off[j] = k_key(j) * rb + ch * 16;
     }
     const uint32_t k_lds_base = lds_offset_of(k_lds);
     int kfrag_off[G];
@@ -137,7 +147,7 @@ void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
         const int key = v_key(j);
         const int ch = (wave + NW * j) >> 1;
         const int pos = (key & ~12) | ((key & 4) << 1) | ((key & 8) >> 1);   // bits 2 and 3 swapped
-        v_off[j] = key * DB + ch * 16;
+        v_off[j] = key * rb + ch * 16;
         v_ldsoff[j] = ch * 8 * VT_PITCH + pos * 2;
     }
     // Vt fragment of (block dvb, sub-tile u, group m): row dvb*32 + l32, keys u*32 + 16m + 8*half ..
@@ -147,24 +157,25 @@ void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
     // rows past the end exist only in the last tile of a TAIL problem: there every row index is clamped
     // (the row a transfer reads moves, its place in LDS does not)
     auto k_issue = [&](int tile, int buf) __attribute__((always_inline)) {
-        const char* tile_base = Kh + (int64_t)tile * (BN * DB);
+        const char* tile_base = Kh + (int64_t)tile * BN * rb;
         const bool clamp = TAIL && tile == n_tiles - 1;
 #pragma unroll
         for (int i = 0; i < K_LOADS; ++i) {
             const char* src = tile_base + k_off[i];
-            if (clamp) src -= (int64_t)(tile * BN + k_key(i) - row_in(tile * BN + k_key(i))) * DB;
+            if (clamp) src -= (int64_t)(tile * BN + k_key(i) - row_in(tile * BN + k_key(i))) * rb;
             dma16_untracked(src, k_lds_base + buf * K_TILE_BYTES + (wave + NW * i) * 1024);
         }
     };
     u32x4 vreg[V_LOADS];
     auto v_load = [&](int tile) __attribute__((always_inline)) {
-        const char* tile_base = Vh + (int64_t)tile * (BN * DB);
+        const char* tile_base = Vh + (int64_t)tile * BN * rb;
         const bool clamp = TAIL && tile == n_tiles - 1;
 #pragma unroll
         for (int j = 0; j < V_LOADS; ++j) {
             const char* src = tile_base + v_off[j];
-            if (clamp) src -= (int64_t)(tile * BN + v_key(j) - row_in(tile * BN + v_key(j))) * DB;
-            vreg[j] = *reinterpret_cast<const u32x4*>(src);
+            if (clamp) src -= (int64_t)(tile * BN + v_key(j) - row_in(tile * BN + v_key(j))) * rb;
+            if (PAD && (int)(((wave + NW * j) >> 1) * 16) >= rb) vreg[j] = u32x4{0u, 0u, 0u, 0u};   // columns past the end
+            else vreg[j] = *reinterpret_cast<const u32x4*>(src);
         }
     };
     auto v_scatter = [&](int buf) __attribute__((always_inline)) {
@@ -301,21 +312,22 @@ void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
     for (int qb = 0; qb < QB; ++qb) {
         const float inv = 1.0f / half_sum(l_run[qb]);
         if (TAIL && q0 + qb * 32 + l32 >= N) continue;
-        char* orow = Oh + (int64_t)(q0 + qb * 32 + l32) * DB + half * 8;
+        char* orow = Oh + (int64_t)(q0 + qb * 32 + l32) * rb + half * 8;
 #pragma unroll
         for (int b = 0; b < DVB; ++b)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 u32x2 w = {pack_bf16x2(oacc[qb][b][4 * i] * inv, oacc[qb][b][4 * i + 1] * inv),
                            pack_bf16x2(oacc[qb][b][4 * i + 2] * inv, oacc[qb][b][4 * i + 3] * inv)};
-                *reinterpret_cast<u32x2*>(orow + (b * 32 + 8 * i) * 2) = w;
+                // (d is a multiple of 16: a run of four columns lies inside the row or past it)
+                if (!PAD || (b * 32 + 8 * i) * 2 + half * 8 < rb) *reinterpret_cast<u32x2*>(orow + (b * 32 + 8 * i) * 2) = w;
             }
     }
 }
 
-template <int DB, int QB, bool TAIL>
+template <int DB, int QB, bool TAIL, bool PAD = false>
 hipError_t launch_attention_t(const void* Q, const void* K, const void* V, void* O, int64_t BH, int N, float scale,
-                              hipStream_t stream)
+                              hipStream_t stream, int d = DB / 2)
 {
     using C = AttnCfg<DB, QB>;
     const uint32_t strips = (uint32_t)((N + C::BM - 1) / C::BM);
@@ -323,9 +335,9 @@ hipError_t launch_attention_t(const void* Q, const void* K, const void* V, void*
     const uint32_t grid = (uint32_t)((total + 7) / 8 * 8);
     const float c = fabsf(scale) * kLog2e;
     const uint32_t flip = scale < 0.0f ? Mma<uint16_t>::kSignMask : 0u;
-    hipLaunchKernelGGL((attention_kernel<DB, QB, TAIL>), dim3(grid), dim3(512), 0, stream, static_cast<const uint16_t*>(Q),
-                       static_cast<const uint16_t*>(K), static_cast<const uint16_t*>(V), static_cast<uint16_t*>(O), N, c,
-                       flip, strips, (uint32_t)total);
+    hipLaunchKernelGGL((attention_kernel<DB, QB, TAIL, PAD>), dim3(grid), dim3(512), 0, stream, static_cast<const uint16_t*>(Q),
+                       static_cast<const uint16_t*>(K), static_cast<const uint16_t*>(V), static_cast<uint16_t*>(O), N, 2 * d,
+                       c, flip, strips, (uint32_t)total);
     return hipGetLastError();
 }
 
@@ -333,7 +345,7 @@ hipError_t launch_attention_t(const void* Q, const void* K, const void* V, void*
 
 bool attention_supported(int64_t BH, int64_t N, int64_t d)
 {
-    if (d != 32 && d != 64 && d != 128) return false;
+    if (d < 16 || d > 128 || (d % 16) != 0) return false;
     if (N < 1 || N > ((int64_t)1 << 24)) return false;
     return BH * ((N + 255) / 256) <= (int64_t)0x7ffffff0;
 }
@@ -341,6 +353,12 @@ bool attention_supported(int64_t BH, int64_t N, int64_t d)
 hipError_t launch_attention(const void* Q, const void* K, const void* V, void* O, int64_t BH, int64_t N, int64_t d,
                             float scale, hipStream_t stream)
 {
+    // head sizes between the powers of two: rows padded on chip, in the instantiation that also takes any length
+    if (d != 32 && d != 64 && d != 128) {
+        if (d <= 32) return launch_attention_t<64, 1, true, true>(Q, K, V, O, BH, (int)N, scale, stream, (int)d);
+        if (d <= 64) return launch_attention_t<128, 1, true, true>(Q, K, V, O, BH, (int)N, scale, stream, (int)d);
+        return launch_attention_t<256, 1, true, true>(Q, K, V, O, BH, (int)N, scale, stream, (int)d);
+    }
     if (d == 32) {          // short rows: two query blocks per wave whenever that leaves enough workgroups
         const bool wide = N >= 2048 && BH * ((N + 511) / 512) >= 200;
         if ((N % 256) != 0)

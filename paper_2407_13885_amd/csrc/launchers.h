@@ -42,7 +42,7 @@ hipError_t launch_qk_gang(const void* Q, const void* K, void* out, int64_t BH, i
 // Y = scale * X over count elements, rounded once to the storage type; X == Y allowed.
 hipError_t launch_scale(DType dt, const void* X, void* Y, int64_t count, float scale, hipStream_t stream);
 
-// Attention output O = softmax(scale Q K^T) V, bf16, d = 32, 64 or 128, any N >= 1.
+// Attention output O = softmax(scale Q K^T) V, bf16, d a multiple of 16 up to 128, any N >= 1.
 bool attention_supported(int64_t BH, int64_t N, int64_t d);
 hipError_t launch_attention(const void* Q, const void* K, const void* V, void* O, int64_t BH, int64_t N, int64_t d,
                             float scale, hipStream_t stream);

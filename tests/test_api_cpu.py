@@ -102,7 +102,8 @@ def test_attention_validation(lib):
     assert a(QA, KA, None, OA, 1, 1, 256, 64, 0.125, BF16, None) == E_NULL
     assert a(QA, KA, VA, None, 1, 1, 256, 64, 0.125, BF16, None) == E_NULL
     assert a(QA, KA, VA, OA, 1, 1, 256, 64, 0.125, F32, None) == E_UNSUP        # bf16 only so far
-    assert a(QA, KA, VA, OA, 1, 1, 256, 96, 0.125, BF16, None) == E_UNSUP       # d = 32, 64 or 128
+    assert a(QA, KA, VA, OA, 1, 1, 256, 144, 0.125, BF16, None) == E_UNSUP      # d a multiple of 16 up to 128
+    assert a(QA, KA, VA, OA, 1, 1, 256, 24, 0.125, BF16, None) == E_UNSUP
     assert a(QA, KA, VA + 2, OA, 1, 1, 256, 64, 0.125, BF16, None) == E_ALIGN
     assert a(QA, KA, VA, VA, 1, 1, 256, 64, 0.125, BF16, None) == E_ALIAS
     assert a(QA, KA, VA, QA + 256 * 64 * 2 - 16, 1, 1, 256, 64, 0.125, BF16, None) == E_ALIAS

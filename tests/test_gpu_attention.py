@@ -76,6 +76,19 @@ def test_attention_any_length(N, d):
         _check_rows(O[0, h], x, V, 0, h, (0, N), f"attention N={N} d={d} head {h}")
 
 
+@pytest.mark.parametrize("d", [16, 48, 80, 96, 112])
+@pytest.mark.parametrize("N", [1, 33, 128, 257, 512, 1000, 1024])
+def test_attention_head_sizes_between_the_powers_of_two(N, d):
+    """Rows of Q, K, V and O that are not 64, 128 or 256 bytes long are padded on chip: zero Q fragments and V
+    columns past the end, output columns past the end not stored (the guard band around O stays untouched)."""
+    x = wl.fused_inputs("t", "bf16", 2, 2, N, d, seed=1900 + N + d, row_factor=(0.5, 2.0))
+    V = wl.value_inputs(x, seed=1901 + N)
+    O = gu.to_f64(_run(x, V))
+    for b in range(2):
+        for h in range(2):
+            _check_rows(O[b, h], x, V, b, h, (0, N), f"attention N={N} d={d} head ({b},{h})")
+
+
 @pytest.mark.parametrize("B,H,N,d", [(1, 40, 2100, 64), (1, 3, 2100, 64), (1, 3, 2300, 128), (1, 40, 2100, 32)])
 def test_attention_any_length_long(B, H, N, d):
     """Ragged lengths of many tiles: only the last tile is compiled with key masks and clamped loads.  40 heads
