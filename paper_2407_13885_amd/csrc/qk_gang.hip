@@ -72,7 +72,7 @@ struct GangCfg {
     static constexpr int K_CHUNKS_PER_LANE = K_BYTES / 16 / (64 * NW);
     static constexpr int K_BATCH = 4;             // chunks per lane in flight while K is copied
     static constexpr int SEG = 128;               // bytes of one staged row: the wave's 64 keys
-    static constexpr int ST_ROWS = (NW == 4 && DB == 256) ? 8 : 16;   // queries staged at a time (what the LDS has room for)
+    static constexpr int ST_ROWS = DB == 256 ? 8 : 16;   // queries staged at a time (what the LDS has room for)
     static constexpr int ST_PITCH = SEG + 16;
     static constexpr int ST_BYTES = ST_ROWS * ST_PITCH;
     static constexpr int CPS = SEG / 16;          // chunks per staged row
@@ -553,11 +553,11 @@ hipError_t launch_gang(const void* Q, const void* K, void* out, int64_t BH, int 
 bool qk_gang_supported(int64_t BH, int64_t N, int64_t d)
 {
     // rows of 128 or 256 bytes; whole key ranges of 256 keys (up to 4096 keys: 16 workgroups of four waves, two per
-    // compute unit) or of 512 (d = 64, up to 16384 keys: 32 workgroups of eight waves); at least two ranges
+    // compute unit) or of 512 (up to 16384 keys: 32 workgroups of eight waves); at least two ranges
     if (d != 64 && d != 128) return false;
     if (compute_units() % 8 != 0 || compute_units() < 128) return false;
     const bool small = N % 256 == 0 && N >= 512 && N <= 4096;
-    const bool large = d == 64 && N % 512 == 0 && N > 4096 && N <= 16384;
+    const bool large = N % 512 == 0 && N > 4096 && N <= 16384;
     if (!small && !large) return false;
     return BH * (N / 32) <= (int64_t)0x7ffffff0;
 }
@@ -568,7 +568,8 @@ hipError_t launch_qk_gang(const void* Q, const void* K, void* out, int64_t BH, i
     if (N <= 4096)
         return d == 64 ? launch_gang<128, 4>(Q, K, out, BH, (int)N, scale, stream)
                        : launch_gang<256, 4>(Q, K, out, BH, (int)N, scale, stream);
-    return launch_gang<128, 8>(Q, K, out, BH, (int)N, scale, stream);
+    return d == 64 ? launch_gang<128, 8>(Q, K, out, BH, (int)N, scale, stream)
+                   : launch_gang<256, 8>(Q, K, out, BH, (int)N, scale, stream);
 }
 
 }  // namespace attnw

@@ -31,12 +31,13 @@ def _check_all(x, P, what):
 
 
 # gangs of 2, 3, 5, 8, 16 workgroups of four waves (key ranges of 256, N <= 4096) and of 10, 16 and 32 workgroups of
-# eight waves (key ranges of 512, d = 64 beyond 4096); lists of one strip (fewer strips than gangs), lists that cross
+# eight waves (key ranges of 512, beyond 4096 keys); lists of one strip (fewer strips than gangs), lists that cross
 # heads, lists of a whole head; both head sizes; sharp and flat rows; a negative scale
 @pytest.mark.parametrize("B,H,N,d,scale", [(1, 1, 512, 64, None), (1, 3, 768, 128, None), (3, 3, 1024, 64, -0.2),
                                            (1, 2, 1280, 128, None), (1, 5, 2048, 128, None), (2, 3, 2048, 64, None),
                                            (1, 1, 4096, 128, None), (1, 3, 4096, 64, -0.11), (1, 40, 1024, 128, None),
-                                           (1, 2, 5120, 64, None), (1, 1, 8192, 64, None), (1, 1, 16384, 64, None)])
+                                           (1, 2, 5120, 64, None), (1, 1, 8192, 64, None), (1, 1, 16384, 64, None),
+                                           (1, 1, 4608, 128, None), (1, 2, 8192, 128, -0.09)])
 def test_gang_kernel_against_the_oracle(B, H, N, d, scale):
     x = wl.fused_inputs("t", "bf16", B, H, N, d, seed=7100 + H + N + d, scale=scale, row_factor=(0.5, 3.0))
     P = gu.run_fused(x, guard=8192)
