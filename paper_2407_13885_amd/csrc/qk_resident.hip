@@ -233,18 +233,25 @@ void qk_resident_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restri
         char* const out_lane = out_rows + ((int64_t)(lane / CPS) * N + wave * 32 * NT + (lane % CPS) * 8) * 2;
         static_for<NT / 2>([&](auto pc) __attribute__((always_inline)) {
             constexpr int tp = decltype(pc)::value;
+            // the lane's 32 weights of this pair of pieces, rounded once -- outside the per-block predicate below
+            // (inside it the arithmetic would be issued once per block)
+            u32x2 wv[2][4];
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const f32x16& a = X[2 * tp + u];
+                    wv[u][r4] = u32x2{pack_bf16x2(a[4 * r4] * inv, a[4 * r4 + 1] * inv),
+                                      pack_bf16x2(a[4 * r4 + 2] * inv, a[4 * r4 + 3] * inv)};
+                }
 #pragma unroll
             for (int hb = 0; hb < ST_BLOCKS; ++hb) {   // queries ST_ROWS hb .. + ST_ROWS of the strip
                 if (l32 / ST_ROWS == hb) {
 #pragma unroll
                     for (int u = 0; u < 2; ++u)
 #pragma unroll
-                        for (int r4 = 0; r4 < 4; ++r4) {
-                            const f32x16& a = X[2 * tp + u];
-                            u32x2 w = {pack_bf16x2(a[4 * r4] * inv, a[4 * r4 + 1] * inv),
-                                       pack_bf16x2(a[4 * r4 + 2] * inv, a[4 * r4 + 3] * inv)};
-                            *reinterpret_cast<u32x2*>(st_wr + (u * 32 + 8 * r4) * 2) = w;
-                        }
+                        for (int r4 = 0; r4 < 4; ++r4)
+                            *reinterpret_cast<u32x2*>(st_wr + (u * 32 + 8 * r4) * 2) = wv[u][r4];
                 }
                 wave_sync_lds();                  // some of the lanes wrote, all of them read
                 u32x4 v[NF];
