@@ -9,7 +9,11 @@
 // the reference moves -- and one sweep over the K and V tiles suffices.
 //
 // Work split: one workgroup of 8 waves per (head, strip of 8 * QW queries); every wave owns
-// QW = 32 * QB queries and walks ALL keys, so no statistics cross waves.  Per 128-key tile:
+// QW = 32 * QB queries and walks ALL keys, so no statistics cross waves.  (Problems of a few heads, the
+// sizes the paper itself measures, have too few such strips for the chip: there the 8 waves are 2 query
+// blocks x 4 key ranges -- a wave takes one 32-key sub-tile of every tile, and the four partial outputs
+// of a query block, each with its own reference exponent and sum, are merged through LDS at the end.)
+// Per 128-key tile:
 //   K tile  [128 keys][d]      global -> LDS directly, chunk-swizzled as in the weight kernels;
 //   V tile  transposed on the way into LDS as Vt[d][128 keys]: the second contraction runs over
 //           keys, and a matrix-core operand wants its 8 contraction elements contiguous per lane.
@@ -47,12 +51,13 @@ __device__ __forceinline__ float half_sum(float x)
 #endif
 }
 
-template <int DB, int QB>
+template <int DB, int QB, int WK = 1>
 struct AttnCfg {
     static constexpr int D = DB / 2;              // head dimension
     static constexpr int NW = 8;
+    static constexpr int WQ = NW / WK;            // waves along the queries (WK: waves that share a query block)
     static constexpr int QW = 32 * QB;            // queries per wave
-    static constexpr int BM = QW * NW;            // queries per workgroup
+    static constexpr int BM = QW * WQ;            // queries per workgroup
     static constexpr int BN = 128;                // keys per tile
     static constexpr int G = DB / 32;             // 32-byte contraction groups per K row
     static constexpr int CPR = DB / 16;           // 16-byte chunks per K / V row
@@ -64,7 +69,11 @@ struct AttnCfg {
     static constexpr int VT_BYTES = D * VT_PITCH;
     static constexpr int RPL = CPR >= 16 ? 1 : 16 / CPR;
     static constexpr int SWZ_MASK = (CPR >= 16 ? 16 : CPR) - 1;
-    static constexpr int LDS_TOTAL = 2 * K_TILE_BYTES + 2 * VT_BYTES;
+    // merging the WK partial results of a query block: per wave, reference exponent, sum and output accumulators
+    static constexpr int MERGE_SLOTS = 2 + DVB * 16;
+    static constexpr int MERGE_BYTES = WK > 1 ? NW * MERGE_SLOTS * 64 * 4 : 0;
+    static constexpr int TILE_BYTES = 2 * K_TILE_BYTES + 2 * VT_BYTES;
+    static constexpr int LDS_TOTAL = TILE_BYTES > MERGE_BYTES ? TILE_BYTES : MERGE_BYTES;
 };
 
 // TAIL: N is not a whole number of tiles / strips.  Rows past the end are read as row N-1 (every load
@@ -72,18 +81,19 @@ struct AttnCfg {
 // PAD:  rows of Q, K, V and O are `rb` < DB bytes long (head sizes that are not 32, 64 or 128); on chip they are
 // padded to DB: Q fragments and V columns past the end are zeros, K chunks past the end hold a copy of the row's
 // first chunk (finite, and it meets the zero Q fragments), output columns past the end are not stored.
-template <int DB, int QB, bool TAIL, bool PAD = false>
+template <int DB, int QB, bool TAIL, bool PAD = false, int WK = 1>
 __global__ __launch_bounds__(512)
 void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
                       uint16_t* __restrict__ O, int N, int rb_arg, float c, uint32_t sign_flip, uint32_t strips, uint32_t total)
 {
     const int rb = PAD ? rb_arg : DB;             // bytes of a row in memory
-    using C = AttnCfg<DB, QB>;
+    using C = AttnCfg<DB, QB, WK>;
     constexpr int NW = C::NW, QW = C::QW, BM = C::BM, BN = C::BN, G = C::G, CPR = C::CPR, DVB = C::DVB;
     constexpr int K_TILE_BYTES = C::K_TILE_BYTES, K_LOADS = C::K_LOADS, V_LOADS = C::V_LOADS;
     constexpr int VT_PITCH = C::VT_PITCH, VT_BYTES = C::VT_BYTES;
     static_assert(2 * K_TILE_BYTES <= 65536, "the K buffers sit in the first 64 KiB of LDS (transfer base register)");
     static_assert((2 * CPR) % NW == 0, "V tile load shape");
+    static_assert(WK == 1 || (QB == 1 && 4 % WK == 0), "key ranges: whole sub-tiles of a tile, one query block per wave");
 
     __shared__ __align__(1024) char lds[C::LDS_TOTAL];
     char* const k_lds = lds;
@@ -104,7 +114,8 @@ void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
     const char* Kh = reinterpret_cast<const char*>(K) + (int64_t)bh * N * rb;
     const char* Vh = reinterpret_cast<const char*>(V) + (int64_t)bh * N * rb;
     char* Oh = reinterpret_cast<char*>(O) + (int64_t)bh * N * rb;
-    const int q0 = strip * BM + wave * QW;
+    const int wq = wave / WK, wk = wave % WK;     // query block of the wave, its key range within every tile
+    const int q0 = strip * BM + wq * QW;
 
     auto row_in = [&](int r) __attribute__((always_inline)) { return TAIL ? min(r, N - 1) : r; };
 
@@ -209,7 +220,8 @@ void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
         const char* kb = k_lds + BUF * K_TILE_BYTES;
         const char* vb = vt_lds + BUF * VT_BYTES + vfrag_off;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int uu = 0; uu < 4 / WK; ++uu) {
+            const int u = wk + WK * uu;           // sub-tiles of this wave
             u32x4 kf[G];
 #pragma unroll
             for (int g = 0; g < G; ++g) kf[g] = *reinterpret_cast<const u32x4*>(kb + u * 32 * DB + kfrag_off[g]);
@@ -307,6 +319,50 @@ void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
         }
     }
 
+    // ---- key ranges: merge the WK partial results of a query block ------------------------------------------------
+    // Every wave parks its reference exponent, its sum and its accumulators in LDS (the tile buffers are free: the
+    // sweep ended with a barrier); wave (wq, wk) then finishes output blocks wk, wk + WK, ..: with M the largest of
+    // the WK exponents, partial j counts with the factor 2^(m_j - M) -- exactly 1 for the largest.
+    if constexpr (WK > 1) {
+        constexpr int SLOTS = C::MERGE_SLOTS;
+        float* const part = reinterpret_cast<float*>(lds);
+        float* const mine = part + wave * SLOTS * 64 + lane;
+        mine[0] = mb_run[0];
+        mine[64] = l_run[0];
+#pragma unroll
+        for (int b = 0; b < DVB; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) mine[(2 + b * 16 + r) * 64] = oacc[0][b][r];
+        __syncthreads();
+        const float* const grp = part + wq * WK * SLOTS * 64 + lane;
+        float f[WK], M = grp[0];
+#pragma unroll
+        for (int j = 1; j < WK; ++j) M = fmaxf(M, grp[j * SLOTS * 64]);
+        float L = 0.0f;
+#pragma unroll
+        for (int j = 0; j < WK; ++j) {
+            f[j] = fast_exp2(grp[j * SLOTS * 64] - M);
+            L = __builtin_fmaf(f[j], grp[j * SLOTS * 64 + 64], L);
+        }
+        const float inv = 1.0f / half_sum(L);
+        if (TAIL && q0 + l32 >= N) return;        // (no barrier follows)
+        char* orow = Oh + (int64_t)(q0 + l32) * rb + half * 8;
+        for (int b = wk; b < DVB; b += WK)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float o[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    o[e] = 0.0f;
+#pragma unroll
+                    for (int j = 0; j < WK; ++j) o[e] = __builtin_fmaf(f[j], grp[(j * SLOTS + 2 + b * 16 + 4 * i + e) * 64], o[e]);
+                }
+                u32x2 w = {pack_bf16x2(o[0] * inv, o[1] * inv), pack_bf16x2(o[2] * inv, o[3] * inv)};
+                if (!PAD || (b * 32 + 8 * i) * 2 + half * 8 < rb) *reinterpret_cast<u32x2*>(orow + (b * 32 + 8 * i) * 2) = w;
+            }
+        return;
+    }
+
     // ---- normalise, round once, store: a lane owns runs of 4 consecutive output columns of its query -----------
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
@@ -325,23 +381,32 @@ void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
     }
 }
 
-template <int DB, int QB, bool TAIL, bool PAD = false>
+template <int DB, int QB, bool TAIL, bool PAD = false, int WK = 1>
 hipError_t launch_attention_t(const void* Q, const void* K, const void* V, void* O, int64_t BH, int N, float scale,
                               hipStream_t stream, int d = DB / 2)
 {
-    using C = AttnCfg<DB, QB>;
+    using C = AttnCfg<DB, QB, WK>;
     const uint32_t strips = (uint32_t)((N + C::BM - 1) / C::BM);
     const uint64_t total = (uint64_t)BH * strips;
     const uint32_t grid = (uint32_t)((total + 7) / 8 * 8);
     const float c = fabsf(scale) * kLog2e;
     const uint32_t flip = scale < 0.0f ? Mma<uint16_t>::kSignMask : 0u;
-    hipLaunchKernelGGL((attention_kernel<DB, QB, TAIL, PAD>), dim3(grid), dim3(512), 0, stream, static_cast<const uint16_t*>(Q),
+    hipLaunchKernelGGL((attention_kernel<DB, QB, TAIL, PAD, WK>), dim3(grid), dim3(512), 0, stream, static_cast<const uint16_t*>(Q),
                        static_cast<const uint16_t*>(K), static_cast<const uint16_t*>(V), static_cast<uint16_t*>(O), N, 2 * d,
                        c, flip, strips, (uint32_t)total);
     return hipGetLastError();
 }
 
 }  // namespace
+
+// Problems with at most one 64-query strip per compute unit (twice that for d <= 64): the wide workgroups would leave
+// most of the chip without work.  Measured, bf16, wide -> key ranges over waves: one head of d = 128, N = 1024
+// 32 -> 19 us, 4096 104 -> 55, 16384 398 -> 227; four heads of N = 4096 106 -> 64 (eight: 111 -> 117, not taken);
+// d = 64: one head of N = 4096 70 -> 29, eight heads 75 -> 62, sixteen 85 -> 121 (not taken).
+static bool prefers_key_ranges(int64_t BH, int64_t N, int64_t d)
+{
+    return BH * ((N + 63) / 64) <= (int64_t)compute_units() * (d <= 64 ? 2 : 1);
+}
 
 bool attention_supported(int64_t BH, int64_t N, int64_t d)
 {
@@ -353,6 +418,15 @@ bool attention_supported(int64_t BH, int64_t N, int64_t d)
 hipError_t launch_attention(const void* Q, const void* K, const void* V, void* O, int64_t BH, int64_t N, int64_t d,
                             float scale, hipStream_t stream)
 {
+    // few heads: 64-query strips with the keys of a tile spread over four waves
+    if (prefers_key_ranges(BH, N, d)) {
+        if (d == 32) return launch_attention_t<64, 1, true, false, 4>(Q, K, V, O, BH, (int)N, scale, stream);
+        if (d == 64) return launch_attention_t<128, 1, true, false, 4>(Q, K, V, O, BH, (int)N, scale, stream);
+        if (d == 128) return launch_attention_t<256, 1, true, false, 4>(Q, K, V, O, BH, (int)N, scale, stream);
+        if (d < 32) return launch_attention_t<64, 1, true, true, 4>(Q, K, V, O, BH, (int)N, scale, stream, (int)d);
+        if (d < 64) return launch_attention_t<128, 1, true, true, 4>(Q, K, V, O, BH, (int)N, scale, stream, (int)d);
+        return launch_attention_t<256, 1, true, true, 4>(Q, K, V, O, BH, (int)N, scale, stream, (int)d);
+    }
     // head sizes between the powers of two: rows padded on chip, in the instantiation that also takes any length
     if (d != 32 && d != 64 && d != 128) {
         if (d <= 32) return launch_attention_t<64, 1, true, true>(Q, K, V, O, BH, (int)N, scale, stream, (int)d);

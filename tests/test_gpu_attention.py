@@ -89,6 +89,35 @@ def test_attention_head_sizes_between_the_powers_of_two(N, d):
             _check_rows(O[b, h], x, V, b, h, (0, N), f"attention N={N} d={d} head ({b},{h})")
 
 
+@pytest.mark.parametrize("d", [32, 48, 64, 80, 112, 128])
+@pytest.mark.parametrize("N", [1, 33, 129, 257, 600])
+def test_attention_many_heads_take_the_wide_strips(N, d):
+    """Few heads run on 64-query strips whose keys are spread over four waves (the tests above); with more than two
+    such strips per compute unit the library takes 256-query strips, every wave walking all keys.  Enough heads for
+    that, first, middle and last head checked."""
+    H = 512 // ((N + 63) // 64) + 1
+    x = wl.fused_inputs("t", "bf16", 1, H, N, d, seed=2300 + N + d, row_factor=(0.5, 2.0))
+    V = wl.value_inputs(x, seed=2301 + N)
+    O = gu.to_f64(_run(x, V))
+    assert np.isfinite(O).all()
+    for h in (0, H // 2, H - 1):
+        _check_rows(O[0, h], x, V, 0, h, (0, N), f"attention wide strips N={N} d={d} head {h} of {H}")
+
+
+@pytest.mark.parametrize("B,H,N,d", [(1, 1, 4096, 128), (1, 4, 4096, 128), (2, 4, 4096, 64), (1, 1, 16384, 128), (1, 2, 16384, 32)])
+def test_attention_few_heads_of_many_keys(B, H, N, d):
+    """The sizes the paper measures are single heads: the four partial results of a query block (one per key range,
+    each with its own reference exponent and sum) are merged at the end.  Sampled rows of every head."""
+    x = wl.fused_inputs("t", "bf16", B, H, N, d, seed=2500 + H + N + d, row_factor=(0.5, 2.0))
+    V = wl.value_inputs(x, seed=2501 + N)
+    O = gu.to_f64(_run(x, V))
+    assert np.isfinite(O).all()
+    for b in range(B):
+        for h in range(H):
+            _check_rows(O[b, h], x, V, b, h, [(0, 40), (N // 2 - 3, N // 2 + 30), (N - 65, N)],
+                        f"attention {B}x{H}x{N}x{d} head ({b},{h})")
+
+
 @pytest.mark.parametrize("B,H,N,d", [(1, 40, 2100, 64), (1, 3, 2100, 64), (1, 3, 2300, 128), (1, 40, 2100, 32)])
 def test_attention_any_length_long(B, H, N, d):
     """Ragged lengths of many tiles: only the last tile is compiled with key masks and clamped loads.  40 heads
@@ -140,15 +169,16 @@ def test_attention_full_size_sampled_rows(name):
         _check_rows(O[0, h], x, V, 0, h, rows, f"{name} attention head {h}")
 
 
+@pytest.mark.parametrize("H", [2, 40])          # key ranges over waves / wide strips
 @pytest.mark.parametrize("d,step", [(64, 0.02), (128, 0.02), (64, 0.4), (128, 0.25)])
-def test_attention_scores_climbing_along_the_keys(d, step):
+def test_attention_scores_climbing_along_the_keys(d, step, H):
     """Scores that grow with the key index: every sub-tile brings a new row maximum.  Small steps stay
     inside the window in which the kernel keeps its reference exponent (weights above 1 appear), large
     steps (8 and more nats per 32 keys) force the reference to move at every sub-tile; the last keys
     carry all the weight.  Scores stay within a few hundred: the fp32 score arithmetic resolves
     differences of scores only to 2^-24 of their magnitude."""
     N = 1024
-    x = wl.fused_inputs("t", "bf16", 1, 2, N, d, seed=90 + d)
+    x = wl.fused_inputs("t", "bf16", 1, H, N, d, seed=90 + d)
     # q = e_0 * a (plus noise in the other coordinates), k_j[0] = j * step / (a * scale): score ~ j * step
     a = 4.0
     ramp = (np.arange(N, dtype=np.float64) * step / (a * float(x.scale)))
