@@ -155,11 +155,15 @@ int attnw_scale(const void *X, void *Y, int64_t count, float scale,
  *
  * Q, K, V : [B][H][N][d], read only.      O : [B][H][N][d], written, never read.
  * P is never written to device memory: one sweep over the keys with a running
- * row maximum and sum (Eq. 1 applied incrementally); the weights are rounded to
- * bf16 before they multiply V on the matrix cores, the output once more at the store.
- * Supported so far: dtype ATTNW_BF16, d a multiple of 16 up to 128, any N >= 1
- * (d = 32, 64, 128 with N a multiple of 256 take the fast path; other head sizes
- * are padded on chip, other lengths clamp and mask the rows past the end).
+ * row maximum and sum (Eq. 1 applied incrementally).
+ * ATTNW_BF16: d a multiple of 16 up to 256, any N >= 1.  The weights are rounded
+ * to bf16 before they multiply V on the matrix cores, the output once more at the
+ * store.  (d up to 128 runs tiled through on-chip memory -- d = 32, 64, 128 with N
+ * a multiple of 256 on the fast path, other head sizes padded on chip, other
+ * lengths with the rows past the end clamped and masked; few heads are spread over
+ * the chip by key ranges.  Larger d reads its operands straight from device memory.)
+ * ATTNW_F32: d a multiple of 4 up to 256, any N >= 1.  Both contractions on the
+ * fp32 matrix instruction: fp32 products, sums and weights, no rounding but fp32's.
  * Anything else: ATTNW_ERR_UNSUPPORTED.  O must not overlap Q, K or V.
  * Validation order as for attnw_fused.
  */

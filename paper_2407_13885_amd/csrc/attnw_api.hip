@@ -86,11 +86,15 @@ int attnw_attention(const void* Q, const void* K, const void* V, void* O, int64_
     if (mul_overflows(B, H, &BH) || mul_overflows(BH, N, &elems) || mul_overflows(elems, d, &elems) ||
         mul_overflows(elems, elem_size(dtype), &bytes))
         return ATTNW_ERR_SHAPE;
-    if (dtype != ATTNW_BF16 || !attnw::attention_supported(BH, N, d)) return ATTNW_ERR_UNSUPPORTED;
+    const attnw::DType dt = dtype == ATTNW_F32 ? attnw::DType::F32 : attnw::DType::BF16;
+    const bool tiled = dtype == ATTNW_BF16 && attnw::attention_supported(BH, N, d);
+    if (!tiled && !attnw::attention_general_supported(dt, BH, N, d)) return ATTNW_ERR_UNSUPPORTED;
     if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O)) return ATTNW_ERR_ALIGN;
     if (overlaps(O, bytes, Q, bytes) || overlaps(O, bytes, K, bytes) || overlaps(O, bytes, V, bytes))
         return ATTNW_ERR_ALIAS;
-    const hipError_t e = attnw::launch_attention(Q, K, V, O, BH, N, d, scale, static_cast<hipStream_t>(stream));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const hipError_t e = tiled ? attnw::launch_attention(Q, K, V, O, BH, N, d, scale, st)
+                               : attnw::launch_attention_general(dt, Q, K, V, O, BH, N, d, scale, st);
     return e == hipSuccess ? ATTNW_OK : ATTNW_ERR_LAUNCH;
 }
 

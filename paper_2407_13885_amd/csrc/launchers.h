@@ -42,9 +42,15 @@ hipError_t launch_qk_gang(const void* Q, const void* K, void* out, int64_t BH, i
 // Y = scale * X over count elements, rounded once to the storage type; X == Y allowed.
 hipError_t launch_scale(DType dt, const void* X, void* Y, int64_t count, float scale, hipStream_t stream);
 
-// Attention output O = softmax(scale Q K^T) V, bf16, d a multiple of 16 up to 128, any N >= 1.
+// Attention output O = softmax(scale Q K^T) V, bf16, d a multiple of 16 up to 128, any N >= 1 (tiled through LDS).
 bool attention_supported(int64_t BH, int64_t N, int64_t d);
 hipError_t launch_attention(const void* Q, const void* K, const void* V, void* O, int64_t BH, int64_t N, int64_t d,
                             float scale, hipStream_t stream);
+
+// The same for fp32 (d a multiple of 4 up to 256, contractions on the fp32 matrix instruction) and for bf16 head sizes
+// up to 256: one wave per 32 queries, operands straight from global memory.
+bool attention_general_supported(DType dt, int64_t BH, int64_t N, int64_t d);
+hipError_t launch_attention_general(DType dt, const void* Q, const void* K, const void* V, void* O, int64_t BH, int64_t N,
+                                    int64_t d, float scale, hipStream_t stream);
 
 }  // namespace attnw

@@ -101,9 +101,12 @@ def test_attention_validation(lib):
     assert a(None, None, None, None, 0, 1, 256, 64, 0.125, BF16, None) == OK
     assert a(QA, KA, None, OA, 1, 1, 256, 64, 0.125, BF16, None) == E_NULL
     assert a(QA, KA, VA, None, 1, 1, 256, 64, 0.125, BF16, None) == E_NULL
-    assert a(QA, KA, VA, OA, 1, 1, 256, 64, 0.125, F32, None) == E_UNSUP        # bf16 only so far
-    assert a(QA, KA, VA, OA, 1, 1, 256, 144, 0.125, BF16, None) == E_UNSUP      # d a multiple of 16 up to 128
+    assert a(QA, KA, VA, OA, 1, 1, 256, 272, 0.125, BF16, None) == E_UNSUP      # bf16: d a multiple of 16 up to 256
     assert a(QA, KA, VA, OA, 1, 1, 256, 24, 0.125, BF16, None) == E_UNSUP
+    assert a(QA, KA, VA, OA, 1, 1, 256, 22, 0.125, F32, None) == E_UNSUP        # fp32: d a multiple of 4 up to 256
+    assert a(QA, KA, VA, OA, 1, 1, 256, 260, 0.125, F32, None) == E_UNSUP
+    assert a(QA, KA, VA + 4, OA, 1, 1, 256, 64, 0.125, F32, None) == E_ALIGN
+    assert a(QA, KA, VA, VA, 1, 1, 256, 12, 0.125, F32, None) == E_ALIAS
     assert a(QA, KA, VA + 2, OA, 1, 1, 256, 64, 0.125, BF16, None) == E_ALIGN
     assert a(QA, KA, VA, VA, 1, 1, 256, 64, 0.125, BF16, None) == E_ALIAS
     assert a(QA, KA, VA, QA + 256 * 64 * 2 - 16, 1, 1, 256, 64, 0.125, BF16, None) == E_ALIAS
