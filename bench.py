@@ -365,8 +365,11 @@ SHAPES_QK = [("bf16", 1, 1, 1024, 128), ("bf16", 1, 1, 2048, 128), ("bf16", 1, 1
              ("bf16", 1, 16, 4000, 128), ("bf16", 1, 16, 4104, 128), ("bf16", 1, 16, 4097, 128), ("bf16", 1, 16, 3968, 64),
              ("bf16", 8, 16, 640, 64), ("bf16", 64, 16, 128, 64), ("bf16", 64, 16, 197, 64), ("f32", 1, 16, 2048, 64),
              ("f32", 1, 16, 4000, 64)]
-SHAPES_ATTENTION = [(1, 16, 4096, 128), (1, 16, 4096, 64), (1, 32, 4096, 32), (1, 16, 4000, 128), (1, 40, 2100, 64), (8, 16, 512, 64),
-                    (64, 16, 197, 64), (1, 2, 32768, 128)]
+SHAPES_ATTENTION = [("bf16", 1, 16, 4096, 128), ("bf16", 1, 16, 4096, 64), ("bf16", 1, 32, 4096, 32), ("bf16", 1, 16, 4000, 128),
+                    ("bf16", 1, 40, 2100, 64), ("bf16", 8, 16, 512, 64), ("bf16", 64, 16, 197, 64), ("bf16", 1, 2, 32768, 128),
+                    ("bf16", 1, 1, 1024, 128), ("bf16", 1, 1, 4096, 128), ("bf16", 1, 4, 4096, 128), ("bf16", 1, 1, 16384, 128),
+                    ("bf16", 1, 1, 4096, 64), ("bf16", 1, 16, 4096, 96), ("bf16", 1, 16, 4096, 256), ("bf16", 1, 16, 4096, 192),
+                    ("f32", 1, 16, 4096, 128), ("f32", 1, 16, 4096, 64), ("f32", 1, 16, 4096, 256), ("f32", 8, 16, 512, 64)]
 
 
 def bench_shapes(steps, warmup):
@@ -404,13 +407,13 @@ def bench_shapes(steps, warmup):
                         "hbm_GBps": round(alg / (ev * 1e-3) * 1e-9, 1)})
             print(f"[bench] {out[-1]}", file=sys.stderr, flush=True)
         del Q, K, P
-    for B, H, N, d in SHAPES_ATTENTION:
-        Q = torch.randn(B, H, N, d, device="cuda", dtype=torch.bfloat16)
+    for dt, B, H, N, d in SHAPES_ATTENTION:
+        Q = torch.randn(B, H, N, d, device="cuda", dtype=TD[dt])
         K, V = torch.randn_like(Q), torch.randn_like(Q)
         O = torch.empty_like(Q)
-        _, ev, _, _ = _time_calls(lambda i: attnw.attnw_attention(Q, K, V, O, B, H, N, d, d ** -0.5, attnw.ATTNW_BF16, stream),
+        _, ev, _, _ = _time_calls(lambda i: attnw.attnw_attention(Q, K, V, O, B, H, N, d, d ** -0.5, DT[dt], stream),
                                   1, steps, warmup)
-        out.append({"call": "attnw_attention", "dtype": "bf16", "B": B, "H": H, "N": N, "d": d, "us": round(ev * 1e3, 1),
+        out.append({"call": "attnw_attention", "dtype": dt, "B": B, "H": H, "N": N, "d": d, "us": round(ev * 1e3, 1),
                     "mfma_TFLOPs": round(4.0 * B * H * N * N * d / (ev * 1e-3) * 1e-12, 1)})
         print(f"[bench] {out[-1]}", file=sys.stderr, flush=True)
         del Q, K, V, O
