@@ -53,7 +53,15 @@ namespace {
 //           of its OWN range -- nobody else touches that piece during this launch -- folds the
 //           pairs into the row's maximum and sum and runs pass two over its range, overwriting
 //           the tables with weights.  (The score GEMM needs no statistics: one launch of mode 2.)
-template <typename T, int DB, int QB, int WQ, int WK, int SUBS, bool SCORES, bool FAST, int SPLIT = 0>
+// RING   rows of the output that start on 16-byte boundaries (bf16 N a multiple of 8).  When they do not start on
+//        64-byte boundaries (N not a multiple of 32), a piece of a row as a tile leaves it starts and ends inside
+//        memory lines, and lines written in parts cost a read-modify-write each.  With RING a wave walks whole tiles (WK = 1)
+//        and its staging row is a ring of one tile plus four 16-byte chunks: after a tile the wave stores, of
+//        every row, the 16 chunks that END at the last 64-byte boundary inside what it has computed -- the up
+//        to three chunks behind that boundary stay in the ring and leave with the next tile.  Every store covers
+//        whole lines; only the first and the last line of a row, and the line where the rotated sweep of the
+//        workgroup started, are written in parts.
+template <typename T, int DB, int QB, int WQ, int WK, int SUBS, bool SCORES, bool FAST, int SPLIT = 0, bool RING = false>
 __global__ __launch_bounds__(64 * WQ * WK)
 void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__ out,
                int N, int d, float c, uint32_t sign_flip, uint32_t strips, uint32_t total_tiles, int kc_count)
@@ -69,13 +77,15 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
     constexpr int K_TILE_BYTES = BN * DB;
     constexpr int LOADS = BN * CPR / 64 / NW; // 1-KiB wave loads each wave issues per tile
     constexpr int SEG = 32 * SUBS * ES;       // bytes of one staged row: the wave's keys of one tile
-    constexpr int ST_PITCH = SEG + 16;        // padded against bank conflicts
-    constexpr int ST_BYTES = QW * ST_PITCH;
     constexpr int CPS = SEG / 16;             // chunks per staged row
+    constexpr int RING_CH = CPS + 4;          // RING: chunks of the ring of a row (a tile and the chunks held back)
+    constexpr int ST_PITCH = (RING ? RING_CH * 16 : SEG) + 16;   // padded against bank conflicts
+    constexpr int ST_BYTES = QW * ST_PITCH;
     constexpr int RPI = 64 / CPS;             // staged rows one store instruction covers
     constexpr int RPL = CPR >= 16 ? 1 : 16 / CPR;           // K rows per 256-byte LDS line
     constexpr int SWZ_MASK = (CPR >= 16 ? 16 : CPR) - 1;
     static_assert((BN * CPR) % (64 * NW) == 0 && CPS <= 64 && QW % RPI == 0, "tile shape");
+    static_assert(!RING || (!FAST && SPLIT == 0 && WK == 1 && ES == 2 && CPS % 4 == 0), "ring staging: a wave owns whole tiles of whole lines");
 
     __shared__ __align__(16) char k_lds0[K_TILE_BYTES];   // the two K tile buffers are separate
     __shared__ __align__(16) char k_lds1[K_TILE_BYTES];   // objects: see dma16
@@ -189,6 +199,7 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
     // then stays in L2); aligned rows at an edge -> the same stores predicated; unaligned rows -> one
     // element per lane, a lane-contiguous run of every staged row.  Returns whether the first path ran:
     // only then is the number of store instructions issued known to the wait that follows.
+    const bool wave_has_rows = FAST || qw0 < N;
     const bool vec_ok = FAST || (N % EPC) == 0;
     const bool rows_full = FAST || qw0 + QW <= N;
     // rows that do not start on a 64-byte boundary make every 128-byte piece of a store straddle memory
@@ -196,6 +207,9 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
     const bool past_caches = FAST || (N * ES) % 64 == 0;
     T* const out_lane = out_h + (int64_t)(qw0 + lane / CPS) * N + (lane % CPS) * EPC;
     auto flush_stage = [&](int kseg0) __attribute__((always_inline)) -> bool {
+      if constexpr (RING) {
+        return false;                         // (the ring has its own flush below)
+      } else {
         const bool full = FAST || (rows_full && vec_ok && kseg0 + 32 * SUBS <= N);
         if (full && past_caches) {
 #pragma unroll
@@ -247,9 +261,46 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
             else store_groups(IC<ES>{});
         }
         return full;
+      }
+    };
+    // RING: chunk c of the j-th tile of the sweep sits at ring chunk (CPS j + c) mod RING_CH.  Window of row r after
+    // that tile (tile index t): the CPS chunks that start a(r) chunks before the tile, a(r) = the row's 16-byte
+    // chunk index in memory mod 4 (so that the window starts on a 64-byte boundary); `tail`: the window after that
+    // one, i.e. what the tile has left behind -- after the last tile of a row (whose successor in the rotated sweep
+    // is tile 0) and at the end of the sweep.  The a(r) chunks in front of a tile are in the ring only if the tile
+    // before it in memory was the one before it in the sweep (not at the start of the sweep; before tile 0 lies
+    // the previous row).  A lane takes chunk i = lane % CPS of row lane / CPS of every group of RPI rows.
+    // Returns whether exactly NST unconditional stores were issued.
+    int ring_p = 0;                           // ring chunk of the start of the tile whose values are being staged
+    auto ring_flush = [&](int j, bool tail) __attribute__((always_inline)) -> bool {
+        const int pj = (CPS * j) % RING_CH;
+        const int t = tile_at(j);
+        const bool interior = !tail && j >= 1 && t >= 1 && rows_full && (t + 1) * BN <= N;   // every chunk of every window exists
+#pragma unroll
+        for (int it = 0; it < QW / RPI; ++it) {
+            const int row = it * RPI + lane / CPS;
+            const int i = lane % CPS + (tail ? CPS : 0);
+            T* const row_ptr = out_h + (int64_t)(qw0 + row) * N;
+            const int a = (int)((reinterpret_cast<uintptr_t>(row_ptr) >> 4) & 3);
+            int x = pj - a + i;                // -3 .. 2 CPS + RING_CH
+            x = x < 0 ? x + RING_CH : x;
+            x = x >= RING_CH ? x - RING_CH : x;
+            x = x >= RING_CH ? x - RING_CH : x;
+            const int key0 = t * BN + (i - a) * EPC;
+            const u32x4 v = *reinterpret_cast<const u32x4*>(stage + row * ST_PITCH + x * 16);
+            if (interior) __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(row_ptr + key0));
+            else if (qw0 + row < N && key0 >= 0 && key0 < N && key0 < (t + 1) * BN && (i >= a || j >= 1))   // (N is a multiple of EPC)
+                *reinterpret_cast<u32x4*>(row_ptr + key0) = v;
+        }
+        return interior;
     };
     auto stage_put4 = [&](int qb, int u, int r4, float v0, float v1, float v2, float v3) __attribute__((always_inline)) {
         char* p = stage + (qb * 32 + l32) * ST_PITCH + (u * 32 + 8 * r4 + 4 * half) * ES;
+        if constexpr (RING) {
+            int ch = ring_p + (u * 32 + 8 * r4) * ES / 16;          // wave-uniform
+            ch = ch >= RING_CH ? ch - RING_CH : ch;
+            p = stage + (qb * 32 + l32) * ST_PITCH + ch * 16 + ((8 * r4 + 4 * half) * ES) % 16;
+        }
         if constexpr (ES == 2) {
             u32x2 w = {pack_bf16x2(v0, v1), pack_bf16x2(v2, v3)};
             *reinterpret_cast<u32x2*>(p) = w;
@@ -371,13 +422,28 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
         constexpr bool FLUSH = decltype(flushc)::value != 0;   // the previous tile's are still staged
         const int k0 = tile_at(j) * BN;
         bool counted = false;                                  // exactly NST stores were issued by this body
-        if constexpr (FLUSH) counted = flush_stage(tile_at(j - 1) * BN + wk * SUBS * 32);
-        static_for<SUBS - 1>([&](auto uc) __attribute__((always_inline)) {
-            constexpr int u = decltype(uc)::value;
-            mma_subtile(bufc, wk * SUBS + u + 1, acc_of(IC<B * SUBS + u + 1>{}));
-            if constexpr (WRITE) emit(acc_of(IC<B * SUBS + u>{}), u);
-            else fold_stats(acc_of(IC<B * SUBS + u>{}), k0 + (wk * SUBS + u) * 32 + 4 * half, tailc);
-        });
+        if constexpr (FLUSH) {
+            if constexpr (RING) {
+                counted = ring_flush(j - 1, false);
+                if (tile_at(j - 1) == n_tiles - 1) {   // the sweep wraps to tile 0: nothing may stay behind
+                    ring_flush(j - 1, true);
+                    counted = false;
+                }
+            } else {
+                counted = flush_stage(tile_at(j - 1) * BN + wk * SUBS * 32);
+            }
+        }
+        if constexpr (RING) ring_p = (CPS * j) % RING_CH;
+        // (a wave whose queries all lie past the end -- the last strip of a ragged length -- only moves K tiles and
+        //  meets the barriers: the strip then costs its workgroup a fraction of a full one)
+        if (wave_has_rows) {
+            static_for<SUBS - 1>([&](auto uc) __attribute__((always_inline)) {
+                constexpr int u = decltype(uc)::value;
+                mma_subtile(bufc, wk * SUBS + u + 1, acc_of(IC<B * SUBS + u + 1>{}));
+                if constexpr (WRITE) emit(acc_of(IC<B * SUBS + u>{}), u);
+                else fold_stats(acc_of(IC<B * SUBS + u>{}), k0 + (wk * SUBS + u) * 32 + 4 * half, tailc);
+            });
+        }
         // The DMA of tile s+1 is older than this body's stores and memory operations
         // retire in order, so the wait can leave the NST stores in flight.
         if constexpr (FAST && FLUSH) {
@@ -391,9 +457,11 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
         // Pin the transfer here: left alone, the scheduler sinks it to the end of the block,
         // right in front of the wait that needs it, and its whole latency is exposed.
         __builtin_amdgcn_sched_barrier(0);
-        mma_subtile(IC<1 - B>{}, wk * SUBS, acc_of(IC<(1 - B) * SUBS>{}));
-        if constexpr (WRITE) emit(acc_of(IC<B * SUBS + SUBS - 1>{}), SUBS - 1);
-        else fold_stats(acc_of(IC<B * SUBS + SUBS - 1>{}), k0 + (wk * SUBS + SUBS - 1) * 32 + 4 * half, tailc);
+        if (wave_has_rows) {
+            mma_subtile(IC<1 - B>{}, wk * SUBS, acc_of(IC<(1 - B) * SUBS>{}));
+            if constexpr (WRITE) emit(acc_of(IC<B * SUBS + SUBS - 1>{}), SUBS - 1);
+            else fold_stats(acc_of(IC<B * SUBS + SUBS - 1>{}), k0 + (wk * SUBS + SUBS - 1) * 32 + 4 * half, tailc);
+        }
     };
     // pass-one body of tile j: the instantiation with key masks only where the tile runs past N
     auto stats_body = [&](int j, auto bufc) __attribute__((always_inline)) {
@@ -466,7 +534,12 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
     if (b0 == 0) body(0, IC<0>{}, IC<1>{}, IC<0>{}, IC<0>{}); else body(0, IC<1>{}, IC<1>{}, IC<0>{}, IC<0>{});
     for_tiles(1, b0 ^ 1, n_tiles, [&](int j, auto bufc) __attribute__((always_inline)) { body(j, bufc, IC<1>{}, IC<1>{}, IC<0>{}); });
     wait_vmem();
-    flush_stage(tile_at(n_tiles - 1) * BN + wk * SUBS * 32);
+    if constexpr (RING) {
+        ring_flush(n_tiles - 1, false);
+        ring_flush(n_tiles - 1, true);        // the chunks held back behind the last 64-byte boundary
+    } else {
+        flush_stage(tile_at(n_tiles - 1) * BN + wk * SUBS * 32);
+    }
 }
 
 // Key ranges per strip for a problem of `units` (head, strip) pairs whose rows have n_tiles K tiles: 1 (no
@@ -537,6 +610,30 @@ hipError_t launch_shape(bool scores_only, const void* Q, const void* K, void* ou
     return launch_variant<T, DB, QB, WQ, WK, SUBS, false, SPLITTABLE>(scores_only, Q, K, out, BH, N, d, scale, stream, allow_split);
 }
 
+// bf16 rows of the output on 16-byte boundaries: 256-query strips, a wave per 32 queries that walks whole 128-key
+// tiles and stores whole memory lines out of a ring (RING in qk_kernel).
+template <int DB>
+hipError_t launch_ring(bool scores_only, const void* Q, const void* K, void* out, int64_t BH, int N, int d, float scale,
+                       hipStream_t stream)
+{
+    constexpr int WQ = 8, BM = 32 * WQ;
+    const uint32_t strips = (uint32_t)((N + BM - 1) / BM);
+    const uint64_t total = (uint64_t)BH * strips;
+    const uint32_t grid = (uint32_t)((total + 7) / 8 * 8);
+    const uint16_t* q = static_cast<const uint16_t*>(Q);
+    const uint16_t* k = static_cast<const uint16_t*>(K);
+    uint16_t* o = static_cast<uint16_t*>(out);
+    const float c = scores_only ? scale : fabsf(scale) * kLog2e;
+    const uint32_t flip = (!scores_only && scale < 0.0f) ? Mma<uint16_t>::kSignMask : 0u;
+    if (scores_only)
+        hipLaunchKernelGGL((qk_kernel<uint16_t, DB, 1, WQ, 1, 4, true, false, 0, true>), dim3(grid), dim3(64 * WQ), 0, stream,
+                           q, k, o, N, d, c, flip, strips, (uint32_t)total, 1);
+    else
+        hipLaunchKernelGGL((qk_kernel<uint16_t, DB, 1, WQ, 1, 4, false, false, 0, true>), dim3(grid), dim3(64 * WQ), 0, stream,
+                           q, k, o, N, d, c, flip, strips, (uint32_t)total, 1);
+    return hipGetLastError();
+}
+
 template <typename T>
 hipError_t launch_qk_t(bool scores_only, const void* Q, const void* K, void* out, int64_t BH, int N, int d,
                        float scale, hipStream_t stream, bool allow_split)
@@ -551,6 +648,19 @@ hipError_t launch_qk_t(bool scores_only, const void* Q, const void* K, void* out
     const bool tables_fit = scores_only || ((int64_t)N * (int64_t)sizeof(T)) % 4 == 0;   // floats in rows of P
     const bool split = allow_split && !big && N >= 1024 && row_bytes > 64 && row_bytes <= 256 && tables_fit &&
                        key_ranges(wide_units, (N + 127) / 128) > 1;
+    if constexpr (sizeof(T) == 2) {
+        // Ragged lengths with rows of P on 16-byte boundaries and enough 256-query strips for the chip: 8 waves of 32
+        // queries that each walk whole tiles and store whole memory lines out of a ring (RING in qk_kernel).
+        // Measured on B1 H16, general kernel -> this one, fused / scores in us: d = 128, N = 2056 223 / 110 -> 88 / 52,
+        // 4072 286 / 215 -> 240 / 168, 8168 1069 / 828 -> 929 / 711, 4104 (a 17th strip of 8 rows) 369 / 242 ->
+        // 340 / 226, 4000 (rows on 64-byte boundaries) 225 / 151 both; d = 64, N = 4072 262 / 209 -> 214 / 165;
+        // B8 H16 N = 648 56 / 33 -> 61 / 37 (not taken: below 1024).
+        if ((N % 8) == 0 && (N % 256) != 0 && N >= 1024 && row_bytes <= 256 && BH * ((N + 255) / 256) >= 100) {
+            if (row_bytes <= 64) return launch_ring<64>(scores_only, Q, K, out, BH, N, d, scale, stream);
+            if (row_bytes <= 128) return launch_ring<128>(scores_only, Q, K, out, BH, N, d, scale, stream);
+            return launch_ring<256>(scores_only, Q, K, out, BH, N, d, scale, stream);
+        }
+    }
     if (row_bytes <= 64)
         return big ? launch_shape<T, 64, QB, 4, 2, 2>(scores_only, Q, K, out, BH, N, d, scale, stream)
                    : launch_shape<T, 64, QB, 1, 2, 2>(scores_only, Q, K, out, BH, N, d, scale, stream);

@@ -83,6 +83,35 @@ def test_fused_ragged_multi_tile(dtype, B, H, N, d):
         assert np.abs(flat.sum(-1) - 1.0).max() <= (gu.ROWSUM_BF16 if dtype == "bf16" else gu.ROWSUM_F32)
 
 
+# ---- ragged lengths with rows of P on 16-byte boundaries (bf16 N a multiple of 8, not of 256, at least 1024) and
+# enough 256-query strips for the chip: whole-line stores out of a ring of staged chunks.  The first tile of a row
+# stores a window that begins before the row (predicated), interior tiles hold back up to three chunks for the next
+# tile, the last tile of a row and the end of the rotated sweep flush what is left; the last strip has waves without
+# rows.  1120 puts rows on 64-byte boundaries (nothing is ever held back), d = 96 and 16 pad the rows of K on chip.
+
+@pytest.mark.parametrize("B,H,N,d", [(1, 20, 1032, 64), (2, 17, 1288, 128), (1, 13, 2056, 128), (1, 20, 1160, 96),
+                                     (1, 25, 1048, 16), (1, 12, 2200, 32), (1, 20, 1120, 64)])
+@pytest.mark.parametrize("what", ["fused", "scores"])
+def test_rows_on_16_byte_boundaries_take_whole_line_stores(B, H, N, d, what):
+    assert N % 8 == 0 and N % 256 != 0 and N >= 1024 and B * H * ((N + 255) // 256) >= 100
+    x = wl.fused_inputs("t", "bf16", B, H, N, d, seed=1700 + N + d, row_factor=(0.5, 2.0))
+    heads = sorted({0, 1, B * H // 2, B * H - 1})
+    Qf, Kf = x.Q.reshape(B * H, N, d), x.K.reshape(B * H, N, d)
+    if what == "fused":
+        got = gu.to_f64(gu.run_fused(x, guard=8192)).reshape(B * H, N, N)
+        for bh in heads:
+            ref = oracle.attention_weights(Qf[bh], Kf[bh], "bf16", x.scale)
+            gu.check_weights(got[bh], ref, "bf16", f"ring {B}x{H}x{N}x{d} head {bh}")
+        assert np.abs(got.sum(-1) - 1.0).max() <= gu.ROWSUM_BF16
+    else:
+        got = gu.to_f64(gu.run_scores(x, guard=8192)).reshape(B * H, N, N)
+        assert np.isfinite(got).all()
+        for bh in heads:
+            ref = oracle.scores(Qf[bh], Kf[bh], "bf16", x.scale)
+            acc = d * 2.0 ** -24 * abs(float(x.scale)) * (np.abs(wl.widen(Qf[bh], "bf16")) @ np.abs(wl.widen(Kf[bh], "bf16")).T)
+            assert (np.abs(got[bh] - ref) <= acc + 2.0 ** -8 * np.abs(ref) + 1e-30).all(), f"ring scores head {bh}"
+
+
 # ---- fused bf16, shapes served by the round-based kernel (N a multiple of 256, d = 64 or 128) ---
 # 600 strips over 256 workgroups: strip lists that cross head boundaries; 20 strips: workgroups
 # with one strip (a statistics round followed directly by a weights round) and idle ones;
