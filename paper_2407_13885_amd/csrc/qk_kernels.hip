@@ -53,15 +53,21 @@ namespace {
 //           of its OWN range -- nobody else touches that piece during this launch -- folds the
 //           pairs into the row's maximum and sum and runs pass two over its range, overwriting
 //           the tables with weights.  (The score GEMM needs no statistics: one launch of mode 2.)
-// RING   rows of the output that start on 16-byte boundaries (bf16 N a multiple of 8).  When they do not start on
-//        64-byte boundaries (N not a multiple of 32), a piece of a row as a tile leaves it starts and ends inside
-//        memory lines, and lines written in parts cost a read-modify-write each.  With RING a wave walks whole tiles (WK = 1)
-//        and its staging row is a ring of one tile plus four 16-byte chunks: after a tile the wave stores, of
-//        every row, the 16 chunks that END at the last 64-byte boundary inside what it has computed -- the up
-//        to three chunks behind that boundary stay in the ring and leave with the next tile.  Every store covers
-//        whole lines; only the first and the last line of a row, and the line where the rotated sweep of the
-//        workgroup started, are written in parts.
-template <typename T, int DB, int QB, int WQ, int WK, int SUBS, bool SCORES, bool FAST, int SPLIT = 0, bool RING = false>
+// RING   (bf16, ragged lengths; 0 = off, else the bytes of one staging write: 8, 4 or 2.)  A piece of a row as a tile
+//        leaves it starts and ends inside memory lines whenever the rows of the output do not start on 64-byte
+//        boundaries, and lines written in parts cost a read-modify-write each; rows that do not even start on
+//        16-byte boundaries (N not a multiple of 8: odd sequence lengths such as 197, 577, 1025) leave only
+//        stores of 8, 4 or 2 bytes per lane.  With RING a wave walks whole tiles (WK = 1) and its staging row is a
+//        ring of 16-byte chunks laid out as the row lies in MEMORY: an element goes to the chunk and the position
+//        it has there (for rows off the 16-byte boundaries that shifts it by up to 7 elements against the tile,
+//        hence the narrower staging writes -- 8 bytes while N is a multiple of 4, 4 while it is even, else 2).
+//        After a tile the wave stores, of every row, the 16 chunks that END at the last 64-byte boundary inside
+//        what it has computed -- the up to three chunks behind that boundary and the chunk that the next tile
+//        completes stay in the ring and leave with the next tile.  Every such store is 16 bytes per lane and
+//        covers whole lines.  Chunks that never become whole -- the two ends of a row, which share their chunk
+//        with the neighbouring rows, and the place where the rotated sweep of the workgroup started -- are
+//        written element by element.
+template <typename T, int DB, int QB, int WQ, int WK, int SUBS, bool SCORES, bool FAST, int SPLIT = 0, int RING = 0>
 __global__ __launch_bounds__(64 * WQ * WK)
 void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__ out,
                int N, int d, float c, uint32_t sign_flip, uint32_t strips, uint32_t total_tiles, int kc_count)
@@ -78,14 +84,15 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
     constexpr int LOADS = BN * CPR / 64 / NW; // 1-KiB wave loads each wave issues per tile
     constexpr int SEG = 32 * SUBS * ES;       // bytes of one staged row: the wave's keys of one tile
     constexpr int CPS = SEG / 16;             // chunks per staged row
-    constexpr int RING_CH = CPS + 4;          // RING: chunks of the ring of a row (a tile and the chunks held back)
-    constexpr int ST_PITCH = (RING ? RING_CH * 16 : SEG) + 16;   // padded against bank conflicts
+    constexpr int RING_CH = CPS + 5;          // RING: chunks of the ring of a row (a tile, the chunks held back, the chunk it shares with the next)
+    constexpr int ST_PITCH = (RING != 0 ? RING_CH * 16 : SEG) + 16;   // padded against bank conflicts
     constexpr int ST_BYTES = QW * ST_PITCH;
     constexpr int RPI = 64 / CPS;             // staged rows one store instruction covers
     constexpr int RPL = CPR >= 16 ? 1 : 16 / CPR;           // K rows per 256-byte LDS line
     constexpr int SWZ_MASK = (CPR >= 16 ? 16 : CPR) - 1;
     static_assert((BN * CPR) % (64 * NW) == 0 && CPS <= 64 && QW % RPI == 0, "tile shape");
-    static_assert(!RING || (!FAST && SPLIT == 0 && WK == 1 && ES == 2 && CPS % 4 == 0), "ring staging: a wave owns whole tiles of whole lines");
+    static_assert(RING == 0 || ((RING == 2 || RING == 4 || RING == 8) && !FAST && SPLIT == 0 && WK == 1 && QB == 1 && ES == 2 && CPS % 4 == 0),
+                  "ring staging: a wave owns whole tiles of whole lines of 32 rows");
 
     __shared__ __align__(16) char k_lds0[K_TILE_BYTES];   // the two K tile buffers are separate
     __shared__ __align__(16) char k_lds1[K_TILE_BYTES];   // objects: see dma16
@@ -207,7 +214,7 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
     const bool past_caches = FAST || (N * ES) % 64 == 0;
     T* const out_lane = out_h + (int64_t)(qw0 + lane / CPS) * N + (lane % CPS) * EPC;
     auto flush_stage = [&](int kseg0) __attribute__((always_inline)) -> bool {
-      if constexpr (RING) {
+      if constexpr (RING != 0) {
         return false;                         // (the ring has its own flush below)
       } else {
         const bool full = FAST || (rows_full && vec_ok && kseg0 + 32 * SUBS <= N);
@@ -263,43 +270,82 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
         return full;
       }
     };
-    // RING: chunk c of the j-th tile of the sweep sits at ring chunk (CPS j + c) mod RING_CH.  Window of row r after
-    // that tile (tile index t): the CPS chunks that start a(r) chunks before the tile, a(r) = the row's 16-byte
-    // chunk index in memory mod 4 (so that the window starts on a 64-byte boundary); `tail`: the window after that
-    // one, i.e. what the tile has left behind -- after the last tile of a row (whose successor in the rotated sweep
-    // is tile 0) and at the end of the sweep.  The a(r) chunks in front of a tile are in the ring only if the tile
-    // before it in memory was the one before it in the sweep (not at the start of the sweep; before tile 0 lies
-    // the previous row).  A lane takes chunk i = lane % CPS of row lane / CPS of every group of RPI rows.
-    // Returns whether exactly NST unconditional stores were issued.
-    int ring_p = 0;                           // ring chunk of the start of the tile whose values are being staged
+    // RING.  With o(r) = the element index of row r's first element in memory mod 8 and a(r) = its 16-byte chunk
+    // index mod 4, element k of the j-th tile of the sweep (tile index t) lies in ring chunk
+    // (CPS j + (k + o) / 8) mod RING_CH at position (k + o) % 8.  Window of row r after that tile: the CPS chunks
+    // that start a(r) chunks before the chunk of the tile's first element, i.e. on a 64-byte boundary; `tail`: the
+    // window after that one, what the tile has left behind -- after the last tile of a row (whose successor in the
+    // rotated sweep is tile 0) and at the end of the sweep.  Chunk i of the window starts at row element
+    // key0 = BN t + 8 (i - a) - o; available are the elements from BN t on (from the tile before on, if that was the
+    // previous one of the sweep) up to the end of the tile or of the row.  A lane takes chunk i = lane % CPS of row
+    // lane / CPS of every group of RPI rows.  Returns whether exactly NST unconditional stores were issued.
+    int ring_p = 0;                           // ring chunk of the first element of the tile whose values are being staged
     auto ring_flush = [&](int j, bool tail) __attribute__((always_inline)) -> bool {
         const int pj = (CPS * j) % RING_CH;
         const int t = tile_at(j);
-        const bool interior = !tail && j >= 1 && t >= 1 && rows_full && (t + 1) * BN <= N;   // every chunk of every window exists
+        const bool chained = j >= 1 && t >= 1;                 // the tile before in memory was the one before in the sweep
+        const bool interior = !tail && chained && rows_full && (t + 1) * BN <= N;   // every chunk of every window is whole
+        const int avail_lo = chained ? -(1 << 20) : t * BN;
+        const int avail_hi = min(N, (t + 1) * BN);
 #pragma unroll
         for (int it = 0; it < QW / RPI; ++it) {
             const int row = it * RPI + lane / CPS;
             const int i = lane % CPS + (tail ? CPS : 0);
             T* const row_ptr = out_h + (int64_t)(qw0 + row) * N;
             const int a = (int)((reinterpret_cast<uintptr_t>(row_ptr) >> 4) & 3);
+            const int o = (int)((reinterpret_cast<uintptr_t>(row_ptr) >> 1) & 7);
             int x = pj - a + i;                // -3 .. 2 CPS + RING_CH
             x = x < 0 ? x + RING_CH : x;
             x = x >= RING_CH ? x - RING_CH : x;
             x = x >= RING_CH ? x - RING_CH : x;
-            const int key0 = t * BN + (i - a) * EPC;
+            const int key0 = t * BN + (i - a) * EPC - o;
             const u32x4 v = *reinterpret_cast<const u32x4*>(stage + row * ST_PITCH + x * 16);
-            if (interior) __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(row_ptr + key0));
-            else if (qw0 + row < N && key0 >= 0 && key0 < N && key0 < (t + 1) * BN && (i >= a || j >= 1))   // (N is a multiple of EPC)
-                *reinterpret_cast<u32x4*>(row_ptr + key0) = v;
+            if (interior) {
+                __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(row_ptr + key0));
+            } else if (qw0 + row < N) {
+                const int lo = max(0, avail_lo - key0), hi = min(EPC, avail_hi - key0);
+                if (lo == 0 && hi == EPC) {
+                    *reinterpret_cast<u32x4*>(row_ptr + key0) = v;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < EPC; ++e)
+                        if (e >= lo && e < hi) row_ptr[key0 + e] = (T)((e & 1) ? (v[e / 2] >> 16) : (v[e / 2] & 0xffffu));
+                }
+            }
         }
         return interior;
     };
+    // the lane's row (QB = 1): where its 4 consecutive keys of a chunk pair land
+    int ring_sel = 0, ring_off = 0;           // s = 4 half + o(r): element s + i of the pair of chunks (B, B + 1)
+    if constexpr (RING != 0) {
+        const int o = (int)((reinterpret_cast<uintptr_t>(out_h + (int64_t)(qw0 + l32) * N) >> 1) & 7);
+        ring_sel = 4 * half + o;
+        ring_off = l32 * ST_PITCH;
+    }
     auto stage_put4 = [&](int qb, int u, int r4, float v0, float v1, float v2, float v3) __attribute__((always_inline)) {
         char* p = stage + (qb * 32 + l32) * ST_PITCH + (u * 32 + 8 * r4 + 4 * half) * ES;
-        if constexpr (RING) {
-            int ch = ring_p + (u * 32 + 8 * r4) * ES / 16;          // wave-uniform
-            ch = ch >= RING_CH ? ch - RING_CH : ch;
-            p = stage + (qb * 32 + l32) * ST_PITCH + ch * 16 + ((8 * r4 + 4 * half) * ES) % 16;
+        if constexpr (RING != 0) {
+            int b0 = ring_p + (u * 32 + 8 * r4) * ES / 16;          // wave-uniform: chunk of the pair's first element for o = 0
+            b0 = b0 >= RING_CH ? b0 - RING_CH : b0;
+            const int b1 = b0 + 1 >= RING_CH ? 0 : b0 + 1;
+            const uint32_t w01 = pack_bf16x2(v0, v1), w23 = pack_bf16x2(v2, v3);
+            char* const rowp = stage + ring_off;
+            auto at = [&](int i) __attribute__((always_inline)) {   // element ring_sel + i
+                const int e = ring_sel + i;
+                return rowp + (e >= 8 ? b1 : b0) * 16 + (e & 7) * 2;
+            };
+            if constexpr (RING == 8) {
+                *reinterpret_cast<u32x2*>(at(0)) = u32x2{w01, w23};
+            } else if constexpr (RING == 4) {
+                *reinterpret_cast<uint32_t*>(at(0)) = w01;
+                *reinterpret_cast<uint32_t*>(at(2)) = w23;
+            } else {
+                *reinterpret_cast<uint16_t*>(at(0)) = (uint16_t)(w01 & 0xffffu);
+                *reinterpret_cast<uint16_t*>(at(1)) = (uint16_t)(w01 >> 16);
+                *reinterpret_cast<uint16_t*>(at(2)) = (uint16_t)(w23 & 0xffffu);
+                *reinterpret_cast<uint16_t*>(at(3)) = (uint16_t)(w23 >> 16);
+            }
+            return;
         }
         if constexpr (ES == 2) {
             u32x2 w = {pack_bf16x2(v0, v1), pack_bf16x2(v2, v3)};
@@ -423,7 +469,7 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
         const int k0 = tile_at(j) * BN;
         bool counted = false;                                  // exactly NST stores were issued by this body
         if constexpr (FLUSH) {
-            if constexpr (RING) {
+            if constexpr (RING != 0) {
                 counted = ring_flush(j - 1, false);
                 if (tile_at(j - 1) == n_tiles - 1) {   // the sweep wraps to tile 0: nothing may stay behind
                     ring_flush(j - 1, true);
@@ -433,7 +479,7 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
                 counted = flush_stage(tile_at(j - 1) * BN + wk * SUBS * 32);
             }
         }
-        if constexpr (RING) ring_p = (CPS * j) % RING_CH;
+        if constexpr (RING != 0) ring_p = (CPS * j) % RING_CH;
         // (a wave whose queries all lie past the end -- the last strip of a ragged length -- only moves K tiles and
         //  meets the barriers: the strip then costs its workgroup a fraction of a full one)
         if (wave_has_rows) {
@@ -534,7 +580,7 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
     if (b0 == 0) body(0, IC<0>{}, IC<1>{}, IC<0>{}, IC<0>{}); else body(0, IC<1>{}, IC<1>{}, IC<0>{}, IC<0>{});
     for_tiles(1, b0 ^ 1, n_tiles, [&](int j, auto bufc) __attribute__((always_inline)) { body(j, bufc, IC<1>{}, IC<1>{}, IC<0>{}); });
     wait_vmem();
-    if constexpr (RING) {
+    if constexpr (RING != 0) {
         ring_flush(n_tiles - 1, false);
         ring_flush(n_tiles - 1, true);        // the chunks held back behind the last 64-byte boundary
     } else {
@@ -610,11 +656,11 @@ hipError_t launch_shape(bool scores_only, const void* Q, const void* K, void* ou
     return launch_variant<T, DB, QB, WQ, WK, SUBS, false, SPLITTABLE>(scores_only, Q, K, out, BH, N, d, scale, stream, allow_split);
 }
 
-// bf16 rows of the output on 16-byte boundaries: 256-query strips, a wave per 32 queries that walks whole 128-key
-// tiles and stores whole memory lines out of a ring (RING in qk_kernel).
-template <int DB>
-hipError_t launch_ring(bool scores_only, const void* Q, const void* K, void* out, int64_t BH, int N, int d, float scale,
-                       hipStream_t stream)
+// bf16, ragged lengths: 256-query strips, a wave per 32 queries that walks whole 128-key tiles and stores whole
+// memory lines out of a ring laid out as the rows lie in memory (RING in qk_kernel).
+template <int DB, int GRAN>
+hipError_t launch_ring_t(bool scores_only, const void* Q, const void* K, void* out, int64_t BH, int N, int d, float scale,
+                         hipStream_t stream)
 {
     constexpr int WQ = 8, BM = 32 * WQ;
     const uint32_t strips = (uint32_t)((N + BM - 1) / BM);
@@ -626,12 +672,21 @@ hipError_t launch_ring(bool scores_only, const void* Q, const void* K, void* out
     const float c = scores_only ? scale : fabsf(scale) * kLog2e;
     const uint32_t flip = (!scores_only && scale < 0.0f) ? Mma<uint16_t>::kSignMask : 0u;
     if (scores_only)
-        hipLaunchKernelGGL((qk_kernel<uint16_t, DB, 1, WQ, 1, 4, true, false, 0, true>), dim3(grid), dim3(64 * WQ), 0, stream,
+        hipLaunchKernelGGL((qk_kernel<uint16_t, DB, 1, WQ, 1, 4, true, false, 0, GRAN>), dim3(grid), dim3(64 * WQ), 0, stream,
                            q, k, o, N, d, c, flip, strips, (uint32_t)total, 1);
     else
-        hipLaunchKernelGGL((qk_kernel<uint16_t, DB, 1, WQ, 1, 4, false, false, 0, true>), dim3(grid), dim3(64 * WQ), 0, stream,
+        hipLaunchKernelGGL((qk_kernel<uint16_t, DB, 1, WQ, 1, 4, false, false, 0, GRAN>), dim3(grid), dim3(64 * WQ), 0, stream,
                            q, k, o, N, d, c, flip, strips, (uint32_t)total, 1);
     return hipGetLastError();
+}
+template <int DB>
+hipError_t launch_ring(bool scores_only, const void* Q, const void* K, void* out, int64_t BH, int N, int d, float scale,
+                       hipStream_t stream)
+{
+    // staging writes as wide as the rows' positions in memory allow (rows start on multiples of 2 N bytes)
+    if (N % 4 == 0) return launch_ring_t<DB, 8>(scores_only, Q, K, out, BH, N, d, scale, stream);
+    if (N % 2 == 0) return launch_ring_t<DB, 4>(scores_only, Q, K, out, BH, N, d, scale, stream);
+    return launch_ring_t<DB, 2>(scores_only, Q, K, out, BH, N, d, scale, stream);
 }
 
 template <typename T>
@@ -649,13 +704,15 @@ hipError_t launch_qk_t(bool scores_only, const void* Q, const void* K, void* out
     const bool split = allow_split && !big && N >= 1024 && row_bytes > 64 && row_bytes <= 256 && tables_fit &&
                        key_ranges(wide_units, (N + 127) / 128) > 1;
     if constexpr (sizeof(T) == 2) {
-        // Ragged lengths with rows of P on 16-byte boundaries and enough 256-query strips for the chip: 8 waves of 32
-        // queries that each walk whole tiles and store whole memory lines out of a ring (RING in qk_kernel).
-        // Measured on B1 H16, general kernel -> this one, fused / scores in us: d = 128, N = 2056 223 / 110 -> 88 / 52,
-        // 4072 286 / 215 -> 240 / 168, 8168 1069 / 828 -> 929 / 711, 4104 (a 17th strip of 8 rows) 369 / 242 ->
-        // 340 / 226, 4000 (rows on 64-byte boundaries) 225 / 151 both; d = 64, N = 4072 262 / 209 -> 214 / 165;
-        // B8 H16 N = 648 56 / 33 -> 61 / 37 (not taken: below 1024).
-        if ((N % 8) == 0 && (N % 256) != 0 && N >= 1024 && row_bytes <= 256 && BH * ((N + 255) / 256) >= 100) {
+        // Ragged lengths with enough 256-query strips for the chip: 8 waves of 32 queries that each walk whole tiles
+        // and store whole memory lines out of a ring (RING in qk_kernel).  Measured, general kernel -> this one,
+        // fused / scores in us.  B1 H16 d128: N = 2056 223 / 110 -> 88 / 52, 4072 286 / 215 -> 240 / 168, 4097 462 / 322 ->
+        // 325 / 201, 4100 398 / 265 -> 294 / 175, 4104 (a 17th strip of 8 rows) 369 / 242 -> 340 / 226, 8168 1069 / 828 ->
+        // 929 / 711; 4000 (rows on 64-byte boundaries) 225 / 151 both.  B8 H16 d64: N = 1543 368 / 283 -> 300 / 213,
+        // 1544 283 / 230 -> 259 / 169, 1284 209 / 157 -> 181 / 119; 1025 193 / 139 -> 182 / 126, B16 H16 N = 785 208 / 152 ->
+        // 179 / 126; not taken: 1032 121 / 78 -> 163 / 104, 1030 144 / 93 -> 164 / 120, B16 H12 N = 577 105 / 77 -> 111 / 84,
+        // B64 H16 N = 197 74 / 53 -> 95 / 77.  Odd lengths gain earlier: their alternative is 2-byte stores.
+        if (N >= ((N & 1) ? 704 : 1280) && (N % 256) != 0 && row_bytes <= 256 && BH * ((N + 255) / 256) >= 100) {
             if (row_bytes <= 64) return launch_ring<64>(scores_only, Q, K, out, BH, N, d, scale, stream);
             if (row_bytes <= 128) return launch_ring<128>(scores_only, Q, K, out, BH, N, d, scale, stream);
             return launch_ring<256>(scores_only, Q, K, out, BH, N, d, scale, stream);
