@@ -658,11 +658,11 @@ hipError_t launch_shape(bool scores_only, const void* Q, const void* K, void* ou
 
 // bf16, ragged lengths: 256-query strips, a wave per 32 queries that walks whole 128-key tiles and stores whole
 // memory lines out of a ring laid out as the rows lie in memory (RING in qk_kernel).
-template <int DB, int GRAN>
+template <int DB, int GRAN, int WQ>
 hipError_t launch_ring_t(bool scores_only, const void* Q, const void* K, void* out, int64_t BH, int N, int d, float scale,
                          hipStream_t stream)
 {
-    constexpr int WQ = 8, BM = 32 * WQ;
+    constexpr int BM = 32 * WQ;
     const uint32_t strips = (uint32_t)((N + BM - 1) / BM);
     const uint64_t total = (uint64_t)BH * strips;
     const uint32_t grid = (uint32_t)((total + 7) / 8 * 8);
@@ -679,14 +679,14 @@ hipError_t launch_ring_t(bool scores_only, const void* Q, const void* K, void* o
                            q, k, o, N, d, c, flip, strips, (uint32_t)total, 1);
     return hipGetLastError();
 }
-template <int DB>
+template <int DB, int WQ = 8>
 hipError_t launch_ring(bool scores_only, const void* Q, const void* K, void* out, int64_t BH, int N, int d, float scale,
                        hipStream_t stream)
 {
     // staging writes as wide as the rows' positions in memory allow (rows start on multiples of 2 N bytes)
-    if (N % 4 == 0) return launch_ring_t<DB, 8>(scores_only, Q, K, out, BH, N, d, scale, stream);
-    if (N % 2 == 0) return launch_ring_t<DB, 4>(scores_only, Q, K, out, BH, N, d, scale, stream);
-    return launch_ring_t<DB, 2>(scores_only, Q, K, out, BH, N, d, scale, stream);
+    if (N % 4 == 0) return launch_ring_t<DB, 8, WQ>(scores_only, Q, K, out, BH, N, d, scale, stream);
+    if (N % 2 == 0) return launch_ring_t<DB, 4, WQ>(scores_only, Q, K, out, BH, N, d, scale, stream);
+    return launch_ring_t<DB, 2, WQ>(scores_only, Q, K, out, BH, N, d, scale, stream);
 }
 
 template <typename T>
@@ -712,6 +712,14 @@ hipError_t launch_qk_t(bool scores_only, const void* Q, const void* K, void* out
         // 1544 283 / 230 -> 259 / 169, 1284 209 / 157 -> 181 / 119; 1025 193 / 139 -> 182 / 126, B16 H16 N = 785 208 / 152 ->
         // 179 / 126; not taken: 1032 121 / 78 -> 163 / 104, 1030 144 / 93 -> 164 / 120, B16 H12 N = 577 105 / 77 -> 111 / 84,
         // B64 H16 N = 197 74 / 53 -> 95 / 77.  Odd lengths gain earlier: their alternative is 2-byte stores.
+        // Odd lengths of a few hundred to a thousand (a class token in front of 24 x 24 or 32 x 32 patches) with d <= 64:
+        // the same with 128-query strips (4 waves, two workgroups per compute unit).  B16 H12 N = 577: d = 64 107 / 77 ->
+        // 98 / 66, d = 32 99 / 72 -> 78 / 58; B8 H16 N = 1025 193 / 139 -> 156 / 110 (182 / 126 with 256-query strips);
+        // B32 H12 N = 257 75 / 53 both; B64 H16 N = 197 74 / 53 -> 91 / 72 (not taken); even lengths lose (578: 79 / 51 -> 84 / 59).
+        if ((N & 1) && N >= 320 && N < 1152 && row_bytes <= 128 && BH * ((N + 127) / 128) >= 200) {
+            if (row_bytes <= 64) return launch_ring<64, 4>(scores_only, Q, K, out, BH, N, d, scale, stream);
+            return launch_ring<128, 4>(scores_only, Q, K, out, BH, N, d, scale, stream);
+        }
         if (N >= ((N & 1) ? 704 : 1280) && (N % 256) != 0 && row_bytes <= 256 && BH * ((N + 255) / 256) >= 100) {
             if (row_bytes <= 64) return launch_ring<64>(scores_only, Q, K, out, BH, N, d, scale, stream);
             if (row_bytes <= 128) return launch_ring<128>(scores_only, Q, K, out, BH, N, d, scale, stream);

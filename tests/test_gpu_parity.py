@@ -99,6 +99,10 @@ def test_fused_ragged_multi_tile(dtype, B, H, N, d):
 @pytest.mark.parametrize("what", ["fused", "scores"])
 def test_rows_on_16_byte_boundaries_take_whole_line_stores(B, H, N, d, what):
     assert N % 256 != 0 and N >= (704 if N % 2 else 1280) and B * H * ((N + 255) // 256) >= 100
+    _ring_case(B, H, N, d, what)
+
+
+def _ring_case(B, H, N, d, what):
     x = wl.fused_inputs("t", "bf16", B, H, N, d, seed=1700 + N + d, row_factor=(0.5, 2.0))
     heads = sorted({0, 1, B * H // 2, B * H - 1})
     Qf, Kf = x.Q.reshape(B * H, N, d), x.K.reshape(B * H, N, d)
@@ -115,6 +119,13 @@ def test_rows_on_16_byte_boundaries_take_whole_line_stores(B, H, N, d, what):
             ref = oracle.scores(Qf[bh], Kf[bh], "bf16", x.scale)
             acc = d * 2.0 ** -24 * abs(float(x.scale)) * (np.abs(wl.widen(Qf[bh], "bf16")) @ np.abs(wl.widen(Kf[bh], "bf16")).T)
             assert (np.abs(got[bh] - ref) <= acc + 2.0 ** -8 * np.abs(ref) + 1e-30).all(), f"ring scores head {bh}"
+
+
+@pytest.mark.parametrize("B,H,N,d", [(4, 50, 577, 64), (2, 60, 333, 32), (1, 100, 1001, 64), (3, 70, 321, 48), (1, 40, 1151, 16)])
+@pytest.mark.parametrize("what", ["fused", "scores"])
+def test_odd_lengths_of_a_few_hundred_take_the_ring_with_128_query_strips(B, H, N, d, what):
+    assert N % 2 == 1 and 320 <= N < 1152 and d <= 64 and B * H * ((N + 127) // 128) >= 200
+    _ring_case(B, H, N, d, what)
 
 
 # ---- fused bf16, shapes served by the round-based kernel (N a multiple of 256, d = 64 or 128) ---
