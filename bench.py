@@ -362,7 +362,9 @@ SHAPES_SOFTMAX = [(1024, 1024), (2048, 2048), (4096, 4096), (8192, 8192), (16384
 # (first five: one head of n x 128, the sizes of the paper's Table I)
 SHAPES_QK = [("bf16", 1, 1, 1024, 128), ("bf16", 1, 1, 2048, 128), ("bf16", 1, 1, 4096, 128), ("bf16", 1, 1, 8192, 128),
              ("bf16", 1, 1, 16384, 128), ("bf16", 1, 2, 4096, 128), ("bf16", 1, 4, 4096, 128), ("bf16", 1, 8, 4096, 128), ("bf16", 1, 16, 4096, 128), ("bf16", 1, 24, 4096, 128), ("bf16", 1, 32, 4096, 128), ("bf16", 1, 16, 4096, 64), ("bf16", 1, 16, 4096, 96), ("bf16", 1, 16, 4096, 256),
-             ("bf16", 1, 16, 4000, 128), ("bf16", 1, 16, 4104, 128), ("bf16", 1, 16, 4097, 128), ("bf16", 1, 16, 3968, 64),
+             ("bf16", 1, 16, 4000, 128), ("bf16", 1, 16, 4072, 128), ("bf16", 1, 16, 4104, 128), ("bf16", 1, 16, 4097, 128),
+             ("bf16", 1, 16, 2056, 128), ("bf16", 1, 16, 3968, 64), ("bf16", 4, 16, 2049, 64), ("bf16", 8, 16, 1025, 64),
+             ("bf16", 16, 12, 577, 64), ("bf16", 16, 12, 576, 64),
              ("bf16", 8, 16, 640, 64), ("bf16", 64, 16, 128, 64), ("bf16", 64, 16, 197, 64), ("f32", 1, 16, 2048, 64),
              ("f32", 1, 16, 4000, 64)]
 SHAPES_ATTENTION = [("bf16", 1, 16, 4096, 128), ("bf16", 1, 16, 4096, 64), ("bf16", 1, 32, 4096, 32), ("bf16", 1, 16, 4000, 128),
