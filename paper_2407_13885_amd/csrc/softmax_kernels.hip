@@ -156,6 +156,109 @@ void softmax_rows_kernel(const TI* S, TO* P, int64_t rows, int groups)   // S ==
     }
 }
 
+// Rows that do not start on 16-byte boundaries (cols not a multiple of the elements per chunk), same type in and
+// out: the matrix is one contiguous array, so a row is still covered by ALIGNED 16-byte chunks -- the first and the
+// last of them shared with the neighbouring rows.  A row is read as those chunks (elements of the neighbours masked
+// out: the softmax does not care where in a chunk an element sits), kept in registers as in softmax_rows_kernel,
+// and written back as whole chunks except the two shared ones, of which only the row's own elements are stored, one
+// by one.  The chunk that would reach past the end of the matrix (last row) is read element by element.
+// chunks of a row <= cols / V + 2 <= R * TPR.
+template <typename T, int R, int TPR>
+__global__ __launch_bounds__(TPR <= 64 ? 256 : TPR)
+void softmax_rows_shifted_kernel(const T* S, T* P, int64_t rows, int cols)   // S == P (in place) is allowed
+{
+    constexpr int V = Elem<T>::VEC;
+    constexpr int WAVES = (TPR <= 64) ? 1 : TPR / 64;
+    constexpr int RPB = (TPR <= 64) ? 256 / TPR : 1;
+    const int tid = (TPR <= 64) ? (int)(threadIdx.x % TPR) : (int)threadIdx.x;
+    const int64_t row = (TPR <= 64) ? (int64_t)blockIdx.x * RPB + (threadIdx.x / TPR) : (int64_t)blockIdx.x;
+    if (row >= rows) return;
+
+    // (S and P are 16-byte aligned: chunk c of the arrays holds elements V c .. V c + V - 1)
+    const int64_t e0 = row * cols;
+    const int64_t c0 = e0 / V;
+    const int rel0 = (int)(c0 * V - e0);                              // -V < rel0 <= 0: the first chunk's first element, relative to the row
+    const int n_chunks = (cols - rel0 + V - 1) / V;
+    const bool last_row = row == rows - 1;                            // its last chunk may reach past the end of the arrays
+    const u32x4* const src = reinterpret_cast<const u32x4*>(S) + c0;
+    u32x4* const dst = reinterpret_cast<u32x4*>(P) + c0;
+
+    float x[R][V];
+    float m = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < R; ++k) {
+        const int c = tid + k * TPR;
+        const int rel = rel0 + c * V;                                 // row index of the chunk's first element
+        const bool mine = c < n_chunks;
+        const bool whole = mine && rel >= 0 && rel + V <= cols;
+        if (__builtin_amdgcn_ballot_w64(mine && !whole) == 0) {       // (wave-uniform) no lane of the wave holds a shared chunk
+            if (mine) Elem<T>::unpack(__builtin_nontemporal_load(src + c), x[k]);
+            else {
+#pragma unroll
+                for (int i = 0; i < V; ++i) x[k][i] = -INFINITY;
+            }
+        } else {
+            float y[V];
+#pragma unroll
+            for (int i = 0; i < V; ++i) y[i] = -INFINITY;
+            if (mine && !(last_row && rel + V > cols)) Elem<T>::unpack(__builtin_nontemporal_load(src + c), y);
+            else if (mine) {
+#pragma unroll
+                for (int i = 0; i < V; ++i)
+                    if ((unsigned)(rel + i) < (unsigned)cols) y[i] = Elem<T>::load1(S + e0 + rel + i);
+            }
+#pragma unroll
+            for (int i = 0; i < V; ++i) x[k][i] = (mine && (unsigned)(rel + i) < (unsigned)cols) ? y[i] : -INFINITY;
+        }
+#pragma unroll
+        for (int i = 0; i < V; ++i) m = fmaxf(m, x[k][i]);
+    }
+
+    __shared__ float red[2][WAVES];
+    m = lanes_reduce_max<TPR>(m);
+    if constexpr (WAVES > 1) {
+        if ((threadIdx.x & 63) == 0) red[0][threadIdx.x >> 6] = m;
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) m = fmaxf(m, red[0][w]);
+    }
+    float l = 0.0f;
+#pragma unroll
+    for (int k = 0; k < R; ++k) {
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+            x[k][i] = fast_exp2((x[k][i] - m) * kLog2e);   // masked elements: 2^-inf = 0
+            l += x[k][i];
+        }
+    }
+    l = lanes_reduce_sum<TPR>(l);
+    if constexpr (WAVES > 1) {
+        if ((threadIdx.x & 63) == 0) red[1][threadIdx.x >> 6] = l;
+        __syncthreads();
+        l = 0.0f;
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) l += red[1][w];
+    }
+    const float inv = 1.0f / l;
+
+#pragma unroll
+    for (int k = 0; k < R; ++k) {
+        const int c = tid + k * TPR;
+        const int rel = rel0 + c * V;
+        const bool mine = c < n_chunks;
+        const bool whole = mine && rel >= 0 && rel + V <= cols;
+#pragma unroll
+        for (int i = 0; i < V; ++i) x[k][i] *= inv;
+        if (whole) {
+            __builtin_nontemporal_store(Elem<T>::pack(x[k]), dst + c);
+        } else if (mine) {
+#pragma unroll
+            for (int i = 0; i < V; ++i)
+                if ((unsigned)(rel + i) < (unsigned)cols) Elem<T>::store1(P + e0 + rel + i, x[k][i]);
+        }
+    }
+}
+
 // EG consecutive elements of type T (EG * sizeof(T) bytes, naturally aligned) <-> floats
 template <typename T, int EG> __device__ __forceinline__ void load_group(const T* p, float* x)
 {
@@ -420,6 +523,17 @@ hipError_t launch_elem_groups(const void* S, void* P, int64_t rows, int cols, hi
     return launch_elem<TI, TO, 16 / EG, 64, EG>(S, P, rows, cols, stream);
 }
 
+template <typename T, int R, int TPR>
+hipError_t launch_rows_shifted(const void* S, void* P, int64_t rows, int64_t cols, hipStream_t stream)
+{
+    constexpr int RPB = (TPR <= 64) ? 256 / TPR : 1;
+    const int64_t blocks = (rows + RPB - 1) / RPB;
+    const int threads = (TPR <= 64) ? 256 : TPR;
+    hipLaunchKernelGGL((softmax_rows_shifted_kernel<T, R, TPR>), dim3((uint32_t)blocks), dim3(threads), 0, stream,
+                       static_cast<const T*>(S), static_cast<T*>(P), rows, (int)cols);
+    return hipGetLastError();
+}
+
 template <typename TI, typename TO>
 hipError_t launch_softmax_t(const void* S, void* P, int64_t rows, int64_t cols, hipStream_t stream)
 {
@@ -442,6 +556,33 @@ hipError_t launch_softmax_t(const void* S, void* P, int64_t rows, int64_t cols, 
         if (groups <= 4096) return launch_rows<TI, TO, 4, 1024>(S, P, rows, groups, stream);
         if constexpr (MAXR >= 16) return launch_rows<TI, TO, 16, 1024>(S, P, rows, groups, stream);
         else return launch_rows<TI, TO, 8, 1024>(S, P, rows, groups, stream);
+    }
+    // rows off the 16-byte boundaries, same type in and out: aligned chunks all the same, the two shared with the
+    // neighbouring rows handled element by element (from 64 columns on: below, the two shared chunks are most of a row)
+    if constexpr (sizeof(TI) == sizeof(TO)) {
+        const int64_t chunks = cols / E + 2;
+        if (cols >= 64 && chunks <= 8192 && (rows + 15) / 16 <= (int64_t)0x7fffffff) {
+            // (a row of 2^k - 1 elements needs 2^k / V or one more chunk: intermediate shapes keep the lanes busy)
+            if (chunks <= 16) return launch_rows_shifted<TI, 1, 16>(S, P, rows, cols, stream);
+            if (chunks <= 32) return launch_rows_shifted<TI, 2, 16>(S, P, rows, cols, stream);
+            if (chunks <= 48) return launch_rows_shifted<TI, 3, 16>(S, P, rows, cols, stream);
+            if (chunks <= 64) return launch_rows_shifted<TI, 2, 32>(S, P, rows, cols, stream);
+            if (chunks <= 96) return launch_rows_shifted<TI, 3, 32>(S, P, rows, cols, stream);
+            if (chunks <= 128) return launch_rows_shifted<TI, 2, 64>(S, P, rows, cols, stream);
+            if (chunks <= 192) return launch_rows_shifted<TI, 3, 64>(S, P, rows, cols, stream);
+            if (chunks <= 256) return launch_rows_shifted<TI, 2, 128>(S, P, rows, cols, stream);
+            if (chunks <= 320) return launch_rows_shifted<TI, 5, 64>(S, P, rows, cols, stream);
+            if (chunks <= 384) return launch_rows_shifted<TI, 3, 128>(S, P, rows, cols, stream);
+            if (chunks <= 512) return launch_rows_shifted<TI, 2, 256>(S, P, rows, cols, stream);
+            if (chunks <= 768) return launch_rows_shifted<TI, 3, 256>(S, P, rows, cols, stream);
+            if (chunks <= 1024) return launch_rows_shifted<TI, 4, 256>(S, P, rows, cols, stream);
+            if (chunks <= 1536) return launch_rows_shifted<TI, 6, 256>(S, P, rows, cols, stream);
+            if (chunks <= 2048) return launch_rows_shifted<TI, 2, 1024>(S, P, rows, cols, stream);
+            if (chunks <= 3072) return launch_rows_shifted<TI, 3, 1024>(S, P, rows, cols, stream);
+            if (chunks <= 4096) return launch_rows_shifted<TI, 4, 1024>(S, P, rows, cols, stream);
+            if (chunks <= 6144) return launch_rows_shifted<TI, 6, 1024>(S, P, rows, cols, stream);
+            return launch_rows_shifted<TI, 8, 1024>(S, P, rows, cols, stream);
+        }
     }
     // short rows of any length and alignment: in registers, in groups of 4, 2 or 1 elements
     if (cols <= 1024) {
