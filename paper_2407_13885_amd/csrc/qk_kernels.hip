@@ -778,6 +778,13 @@ hipError_t launch_qk(DType dt, bool scores_only, const void* Q, const void* K, v
     const bool twopass = force && strcmp(force, "twopass") == 0;
     const bool rounds = force && strcmp(force, "rounds") == 0;
     const bool gang = force && strcmp(force, "gang") == 0;
+    // Short sequences whose length is not a multiple of 32 (d = 64; 197, 257, 577 ...): the kernel that stages a strip
+    // as the contiguous block of P that it is.  Measured against the general kernel, us: B64 H16 N = 33 31 -> 14,
+    // 65 34 -> 20, 100 26 -> 21, 161 66 -> 40, 197 74 -> 50, 200 50 -> 41; B32 H12 N = 257 75 -> 46, 300 52 -> 43; B16 H12
+    // N = 400 40 -> 29, 520 58 -> 44, 577 84 -> 70, 578 78 -> 56, 600 60 -> 52, 607 84 -> 71; one head of N = 197 16 -> 5.5, 577
+    // 34 -> 18.  Multiples of 32 stay where they were (128: 25 against 27, 256: 20 against 25, 320: 47 against 50, 576: 58
+    // against 64).
+    if (!scores_only && !force && (N % 32) != 0 && qk_flat_supported(BH, N, d)) return launch_qk_flat(Q, K, out, BH, N, scale, stream);
     if (!scores_only && qk_gang_supported(BH, N, d) && (gang || (!force && prefers_gang(BH, N, d))))
         return launch_qk_gang(Q, K, out, BH, N, d, scale, stream);
     if (!twopass && !(!rounds && prefers_key_split(BH, N, d))) {

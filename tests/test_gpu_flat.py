@@ -1,0 +1,59 @@
+"""GPU parity of attnw_fused on short sequences of any length (bf16, d = 64, N <= 608: the kernel that stages a strip
+of 32 queries as the contiguous block of P that it is) against the fp64 oracle: every element of sampled heads at the
+bf16 bar, every row sum, the guard bands around P."""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2407_13885_amd import workloads as wl
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _gpu():
+    gu.require_gpu()
+
+
+def _check(B, H, N, scale=None, row_factor=(0.5, 2.0), seed=0):
+    x = wl.fused_inputs("t", "bf16", B, H, N, 64, seed=4100 + N + seed, scale=scale, row_factor=row_factor)
+    got = gu.to_f64(gu.run_fused(x, guard=8192)).reshape(B * H, N, N)
+    Qf, Kf = x.Q.reshape(B * H, N, 64), x.K.reshape(B * H, N, 64)
+    for bh in sorted({0, 1 % (B * H), B * H // 2, B * H - 1}):
+        ref = oracle.attention_weights(Qf[bh], Kf[bh], "bf16", x.scale)
+        gu.check_weights(got[bh], ref, "bf16", f"short sequence {B}x{H}x{N} head {bh}")
+    assert np.isfinite(got).all()
+    assert np.abs(got.sum(-1) - 1.0).max() <= gu.ROWSUM_BF16
+
+
+# odd lengths (2-byte staging writes), even (4-byte), multiples of 4 (8-byte); one to four pieces of keys per wave;
+# lengths with waves that own no key (197: the eighth), with a last strip of one query (33, 65, 257, 577), of 31 (607)
+@pytest.mark.parametrize("N", [1, 2, 3, 31, 33, 65, 100, 197, 198, 200, 255, 257, 258, 260, 333, 511, 513, 577, 578, 580,
+                               601, 607])
+def test_short_sequences_any_length(N):
+    _check(1, 3, N)
+
+
+@pytest.mark.parametrize("B,H,N", [(4, 70, 197), (2, 150, 257), (1, 300, 65), (3, 40, 577), (1, 9, 601)])
+def test_short_sequences_many_heads(B, H, N):
+    """More (head, strip) pairs than workgroups: strip lists that cross head boundaries (the K of the next head
+    replaces the one in LDS in the middle of a list); few heads: several workgroups share a head."""
+    _check(B, H, N)
+
+
+@pytest.mark.parametrize("N", [197, 577])
+@pytest.mark.parametrize("scale", [0.0, -0.125, 0.5])
+def test_short_sequences_scale_values(N, scale):
+    _check(1, 2, N, scale=scale, row_factor=(0.5, 3.0), seed=7)
+
+
+@pytest.mark.parametrize("N", [33, 197, 333, 577])
+def test_the_general_kernel_still_serves_these_lengths(N, monkeypatch):
+    """ATTNW_FUSED_KERNEL=twopass keeps the same problems on the two-pass kernel (its ragged paths at d = 64 would
+    otherwise only be reached by the score GEMM)."""
+    monkeypatch.setenv("ATTNW_FUSED_KERNEL", "twopass")
+    _check(1, 3, N, seed=11)
