@@ -35,7 +35,9 @@ constexpr int kFlatMaxN = 608;                    // 256 N bytes of LDS: K of a 
 // statistics every wave published before the previous barrier, into weights in the block buffer of its parity; after
 // the barrier the block leaves while the next iteration already computes.  Two register sets of exponentials, two
 // statistics buffers, two block buffers.
-template <int NT, int GRAN>
+// SCORES: write scale * Q K^T instead of the weights (the first stage of the unfused pipelines: no statistics, the same
+//         way out); c is then the scale itself
+template <int NT, int GRAN, bool SCORES>
 __global__ __launch_bounds__(512)
 void qk_flat_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, uint16_t* __restrict__ out, int N,
                     float c, uint32_t sign_flip, uint32_t strips_per_head, uint32_t total_strips)
@@ -112,6 +114,7 @@ void qk_flat_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict__
                 for (int g = 0; g < G; ++g)
                     Mma<uint16_t>::run(X[t], *reinterpret_cast<const u32x4*>(piece + frag_off[g]), qf[g]);
             }
+            if constexpr (SCORES) continue;       // (keys past N are never staged)
             if (kp + 32 > N) {                    // (wave-uniform) the one piece that N cuts, and the pieces past it
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
@@ -122,6 +125,7 @@ void qk_flat_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict__
 #pragma unroll
             for (int r = 0; r < 16; r += 2) m = max3(m, X[t][r], X[t][r + 1]);
         }
+        if constexpr (SCORES) return c;           // the factor of every score
         m = fmaxf(m, __shfl_xor(m, 32, 64));      // lanes l and l + 32 hold the two halves of a query's keys
         const float mb = m * c;
         float l = 0.0f;
@@ -153,14 +157,17 @@ void qk_flat_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict__
         const uint32_t bh = strip_id / strips_per_head;
         const int q0 = (int)(strip_id - bh * strips_per_head) * 32;
         const int rows = min(32, N - q0);
-        const float* const st = stat + parity * STAT_FLOATS;
-        float mbg = mb;
+        float inv = mb;                           // SCORES: the scale
+        if constexpr (!SCORES) {
+            const float* const st = stat + parity * STAT_FLOATS;
+            float mbg = mb;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) mbg = fmaxf(mbg, st[w * 32 + l32]);
-        float lg = 0.0f;
+            for (int w = 0; w < NW; ++w) mbg = fmaxf(mbg, st[w * 32 + l32]);
+            float lg = 0.0f;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) lg += st[NW * 32 + w * 32 + l32] * fast_exp2(st[w * 32 + l32] - mbg);
-        const float inv = fast_exp2(mb - mbg) * __builtin_amdgcn_rcpf(lg);
+            for (int w = 0; w < NW; ++w) lg += st[NW * 32 + w * 32 + l32] * fast_exp2(st[w * 32 + l32] - mbg);
+            inv = fast_exp2(mb - mbg) * __builtin_amdgcn_rcpf(lg);
+        }
         const int64_t e0 = ((int64_t)bh * N + q0) * N;                      // first element of the block in P
         const int o = (int)(e0 & 7);
         if (l32 < rows) {
@@ -256,7 +263,7 @@ void qk_flat_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict__
 }
 
 template <int NT, int GRAN>
-hipError_t launch_flat_t(const void* Q, const void* K, void* out, int64_t BH, int N, float scale, hipStream_t stream)
+hipError_t launch_flat_t(bool scores_only, const void* Q, const void* K, void* out, int64_t BH, int N, float scale, hipStream_t stream)
 {
     const uint32_t strips_per_head = (uint32_t)((N + 31) / 32);
     const uint32_t total = (uint32_t)(BH * strips_per_head);
@@ -266,19 +273,23 @@ hipError_t launch_flat_t(const void* Q, const void* K, void* out, int64_t BH, in
     uint32_t grid = (uint32_t)((compute_units() * (NT == 1 ? 2 : 1) + 7) / 8 * 8);
     const uint32_t want = (total + 3) / 4;
     if (grid > want) grid = (want + 7) / 8 * 8;
-    const float c = fabsf(scale) * kLog2e;
-    const uint32_t flip = scale < 0.0f ? Mma<uint16_t>::kSignMask : 0u;
-    hipLaunchKernelGGL((qk_flat_kernel<NT, GRAN>), dim3(grid), dim3(512), 0, stream, static_cast<const uint16_t*>(Q),
-                       static_cast<const uint16_t*>(K), static_cast<uint16_t*>(out), N, c, flip, strips_per_head, total);
+    const float c = scores_only ? scale : fabsf(scale) * kLog2e;
+    const uint32_t flip = (!scores_only && scale < 0.0f) ? Mma<uint16_t>::kSignMask : 0u;
+    if (scores_only)
+        hipLaunchKernelGGL((qk_flat_kernel<NT, GRAN, true>), dim3(grid), dim3(512), 0, stream, static_cast<const uint16_t*>(Q),
+                           static_cast<const uint16_t*>(K), static_cast<uint16_t*>(out), N, c, flip, strips_per_head, total);
+    else
+        hipLaunchKernelGGL((qk_flat_kernel<NT, GRAN, false>), dim3(grid), dim3(512), 0, stream, static_cast<const uint16_t*>(Q),
+                           static_cast<const uint16_t*>(K), static_cast<uint16_t*>(out), N, c, flip, strips_per_head, total);
     return hipGetLastError();
 }
 
 template <int NT>
-hipError_t launch_flat(const void* Q, const void* K, void* out, int64_t BH, int N, float scale, hipStream_t stream)
+hipError_t launch_flat(bool scores_only, const void* Q, const void* K, void* out, int64_t BH, int N, float scale, hipStream_t stream)
 {
-    if (N % 4 == 0) return launch_flat_t<NT, 8>(Q, K, out, BH, N, scale, stream);
-    if (N % 2 == 0) return launch_flat_t<NT, 4>(Q, K, out, BH, N, scale, stream);
-    return launch_flat_t<NT, 2>(Q, K, out, BH, N, scale, stream);
+    if (N % 4 == 0) return launch_flat_t<NT, 8>(scores_only, Q, K, out, BH, N, scale, stream);
+    if (N % 2 == 0) return launch_flat_t<NT, 4>(scores_only, Q, K, out, BH, N, scale, stream);
+    return launch_flat_t<NT, 2>(scores_only, Q, K, out, BH, N, scale, stream);
 }
 
 }  // namespace
@@ -289,11 +300,12 @@ bool qk_flat_supported(int64_t BH, int64_t N, int64_t d)
     return BH * ((N + 31) / 32) <= (int64_t)0x7ffffff0;
 }
 
-hipError_t launch_qk_flat(const void* Q, const void* K, void* out, int64_t BH, int64_t N, float scale, hipStream_t stream)
+hipError_t launch_qk_flat(bool scores_only, const void* Q, const void* K, void* out, int64_t BH, int64_t N, float scale,
+                          hipStream_t stream)
 {
-    if (N <= 256) return launch_flat<1>(Q, K, out, BH, (int)N, scale, stream);
-    if (N <= 512) return launch_flat<2>(Q, K, out, BH, (int)N, scale, stream);
-    return launch_flat<3>(Q, K, out, BH, (int)N, scale, stream);
+    if (N <= 256) return launch_flat<1>(scores_only, Q, K, out, BH, (int)N, scale, stream);
+    if (N <= 512) return launch_flat<2>(scores_only, Q, K, out, BH, (int)N, scale, stream);
+    return launch_flat<3>(scores_only, Q, K, out, BH, (int)N, scale, stream);
 }
 
 }  // namespace attnw

@@ -70,7 +70,7 @@ namespace {
 template <typename T, int DB, int QB, int WQ, int WK, int SUBS, bool SCORES, bool FAST, int SPLIT = 0, int RING = 0>
 __global__ __launch_bounds__(64 * WQ * WK)
 void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__ out,
-               int N, int d, float c, uint32_t sign_flip, uint32_t strips, uint32_t total_tiles, int kc_count)
+               int N, int d, float c, uint32_t sign_flip, uint32_t strips, uint32_t total_tiles, int kc_count, int q_base)
 {
     constexpr int ES = sizeof(T);
     constexpr int EPC = 16 / ES;              // elements per 16-byte chunk
@@ -122,7 +122,9 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
     const char* Qh = reinterpret_cast<const char*>(Q) + (int64_t)bh * N * row_bytes;
     const char* Kh = reinterpret_cast<const char*>(K) + (int64_t)bh * N * row_bytes;
     T* out_h = out + (int64_t)bh * N * N;
-    const int qw0 = strip * BM + wq * QW;     // first query of this wave
+    // (q_base: the launch covers the queries from there on -- the last, partial strip of a ragged length can be a
+    // launch of its own with a workgroup shape that spreads its keys over the waves)
+    const int qw0 = q_base + strip * BM + wq * QW;   // first query of this wave
     char* const stage = st_lds + wave * ST_BYTES;
 
     // ---- Q fragments: registers for the whole kernel --------------------------------
@@ -624,12 +626,12 @@ hipError_t launch_variant(bool scores_only, const void* Q, const void* K, void* 
             const uint32_t grid = (uint32_t)((total + 7) / 8 * 8);
             if (scores_only) {
                 hipLaunchKernelGGL((qk_kernel<T, DB, QB, WQ, WK, SUBS, true, FAST, 2>), dim3(grid), dim3(threads), 0,
-                                   stream, q, k, o, N, d, c, flip, strips, (uint32_t)total, kc);
+                                   stream, q, k, o, N, d, c, flip, strips, (uint32_t)total, kc, 0);
             } else {
                 hipLaunchKernelGGL((qk_kernel<T, DB, QB, WQ, WK, SUBS, false, FAST, 1>), dim3(grid), dim3(threads), 0,
-                                   stream, q, k, o, N, d, c, flip, strips, (uint32_t)total, kc);
+                                   stream, q, k, o, N, d, c, flip, strips, (uint32_t)total, kc, 0);
                 hipLaunchKernelGGL((qk_kernel<T, DB, QB, WQ, WK, SUBS, false, FAST, 2>), dim3(grid), dim3(threads), 0,
-                                   stream, q, k, o, N, d, c, flip, strips, (uint32_t)total, kc);
+                                   stream, q, k, o, N, d, c, flip, strips, (uint32_t)total, kc, 0);
             }
             return hipGetLastError();
         }
@@ -638,10 +640,10 @@ hipError_t launch_variant(bool scores_only, const void* Q, const void* K, void* 
     const uint32_t grid = (uint32_t)((total + 7) / 8 * 8);
     if (scores_only)
         hipLaunchKernelGGL((qk_kernel<T, DB, QB, WQ, WK, SUBS, true, FAST>), dim3(grid), dim3(threads), 0, stream, q, k,
-                           o, N, d, c, flip, strips, (uint32_t)total, 1);
+                           o, N, d, c, flip, strips, (uint32_t)total, 1, 0);
     else
         hipLaunchKernelGGL((qk_kernel<T, DB, QB, WQ, WK, SUBS, false, FAST>), dim3(grid), dim3(threads), 0, stream, q,
-                           k, o, N, d, c, flip, strips, (uint32_t)total, 1);
+                           k, o, N, d, c, flip, strips, (uint32_t)total, 1, 0);
     return hipGetLastError();
 }
 
@@ -663,20 +665,45 @@ hipError_t launch_ring_t(bool scores_only, const void* Q, const void* K, void* o
                          hipStream_t stream)
 {
     constexpr int BM = 32 * WQ;
-    const uint32_t strips = (uint32_t)((N + BM - 1) / BM);
-    const uint64_t total = (uint64_t)BH * strips;
-    const uint32_t grid = (uint32_t)((total + 7) / 8 * 8);
+    uint32_t strips = (uint32_t)((N + BM - 1) / BM);
     const uint16_t* q = static_cast<const uint16_t*>(Q);
     const uint16_t* k = static_cast<const uint16_t*>(K);
     uint16_t* o = static_cast<uint16_t*>(out);
     const float c = scores_only ? scale : fabsf(scale) * kLog2e;
     const uint32_t flip = (!scores_only && scale < 0.0f) ? Mma<uint16_t>::kSignMask : 0u;
+    // The last strip of a ragged length holds N % BM queries, and a workgroup of this shape spends on it what one of
+    // its waves spends on a full strip (the waves without queries only help with the K tiles): about half the
+    // time of a full workgroup.  Where those workgroups make the difference between one more round of workgroups
+    // on the chip and none (N = 4104, 16 heads: 272 workgroups of 256-query strips on 256 compute units), the last
+    // strip becomes a launch of its own: 32-query strips whose keys are spread over the 8 waves of a workgroup.
+    // Measured, fused / scores in us, B1 H16 d = 128: N = 4104 296 / 226 -> 260 / 150, 4097 322 / 201 -> 266 / 169, 4100
+    // 294 / 175 -> 238 / 144, 8200 929 -> 866 (4072, 16 full strips and nothing else: 203 - 210 / 131).
+    const int tail_rows = N % BM;
+    const int64_t slots = (int64_t)compute_units() * (WQ == 8 ? 1 : 2);
+    const int64_t full = BH * (int64_t)(N / BM);
+    const bool own_tail = tail_rows != 0 && tail_rows <= 96 && full > 0 &&
+                          (full + slots - 1) / slots < (full + BH + slots - 1) / slots;
+    if (own_tail) strips -= 1;
+    const uint64_t total = (uint64_t)BH * strips;
+    const uint32_t grid = (uint32_t)((total + 7) / 8 * 8);
     if (scores_only)
         hipLaunchKernelGGL((qk_kernel<uint16_t, DB, 1, WQ, 1, 4, true, false, 0, GRAN>), dim3(grid), dim3(64 * WQ), 0, stream,
-                           q, k, o, N, d, c, flip, strips, (uint32_t)total, 1);
+                           q, k, o, N, d, c, flip, strips, (uint32_t)total, 1, 0);
     else
         hipLaunchKernelGGL((qk_kernel<uint16_t, DB, 1, WQ, 1, 4, false, false, 0, GRAN>), dim3(grid), dim3(64 * WQ), 0, stream,
-                           q, k, o, N, d, c, flip, strips, (uint32_t)total, 1);
+                           q, k, o, N, d, c, flip, strips, (uint32_t)total, 1, 0);
+    if (own_tail) {
+        const uint32_t tail_strips = (uint32_t)((tail_rows + 31) / 32);
+        const uint64_t tail_total = (uint64_t)BH * tail_strips;
+        const uint32_t tail_grid = (uint32_t)((tail_total + 7) / 8 * 8);
+        const int q_base = (int)strips * BM;
+        if (scores_only)
+            hipLaunchKernelGGL((qk_kernel<uint16_t, DB, 1, 1, 8, 1, true, false>), dim3(tail_grid), dim3(512), 0, stream,
+                               q, k, o, N, d, c, flip, tail_strips, (uint32_t)tail_total, 1, q_base);
+        else
+            hipLaunchKernelGGL((qk_kernel<uint16_t, DB, 1, 1, 8, 1, false, false>), dim3(tail_grid), dim3(512), 0, stream,
+                               q, k, o, N, d, c, flip, tail_strips, (uint32_t)tail_total, 1, q_base);
+    }
     return hipGetLastError();
 }
 template <int DB, int WQ = 8>
@@ -784,7 +811,9 @@ hipError_t launch_qk(DType dt, bool scores_only, const void* Q, const void* K, v
     // N = 400 40 -> 29, 520 58 -> 44, 577 84 -> 70, 578 78 -> 56, 600 60 -> 52, 607 84 -> 71; one head of N = 197 16 -> 5.5, 577
     // 34 -> 18.  Multiples of 32 stay where they were (128: 25 against 27, 256: 20 against 25, 320: 47 against 50, 576: 58
     // against 64).
-    if (!scores_only && !force && (N % 32) != 0 && qk_flat_supported(BH, N, d)) return launch_qk_flat(Q, K, out, BH, N, scale, stream);
+    // (scores of even lengths leave the general kernel as fast: its 4-byte stores pair up; measured 100 <= N <= 584)
+    if (!force && (N % 32) != 0 && (!scores_only || (N & 1)) && qk_flat_supported(BH, N, d))
+        return launch_qk_flat(scores_only, Q, K, out, BH, N, scale, stream);
     if (!scores_only && qk_gang_supported(BH, N, d) && (gang || (!force && prefers_gang(BH, N, d))))
         return launch_qk_gang(Q, K, out, BH, N, d, scale, stream);
     if (!twopass && !(!rounds && prefers_key_split(BH, N, d))) {

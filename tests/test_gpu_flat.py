@@ -5,6 +5,7 @@ import os
 
 import numpy as np
 import pytest
+import torch
 
 import oracle
 from paper_2407_13885_amd import workloads as wl
@@ -57,3 +58,28 @@ def test_the_general_kernel_still_serves_these_lengths(N, monkeypatch):
     otherwise only be reached by the score GEMM)."""
     monkeypatch.setenv("ATTNW_FUSED_KERNEL", "twopass")
     _check(1, 3, N, seed=11)
+
+
+def _check_scores(x, S, what):
+    got = gu.to_f64(S)
+    Qa, Ka = np.abs(wl.widen(x.Q, "bf16")), np.abs(wl.widen(x.K, "bf16"))
+    B, H = x.Q.shape[:2]
+    for b in range(B):
+        for h in range(H):
+            ref = oracle.scores(x.Q[b, h], x.K[b, h], "bf16", x.scale)
+            acc_bound = 64 * 2.0 ** -24 * abs(float(x.scale)) * (Qa[b, h] @ Ka[b, h].T)
+            assert (np.abs(got[b, h] - ref) <= acc_bound + 2.0 ** -8 * np.abs(ref) + 1e-30).all(), f"{what} head {b},{h}"
+
+
+@pytest.mark.parametrize("B,H,N,scale", [(1, 3, 1, None), (1, 3, 33, None), (2, 70, 197, None), (1, 3, 198, -0.37),
+                                         (1, 2, 200, 1.0), (1, 150, 257, None), (1, 3, 333, 0.0), (2, 20, 577, None),
+                                         (1, 3, 578, None), (1, 3, 607, -1.0)])
+def test_scaled_scores_of_short_sequences(B, H, N, scale, monkeypatch):
+    """attnw_gemm_scores on the same lengths: the same kernel without the statistics.  Against the oracle, the
+    guard bands around S, and bit for bit against the general kernel (same order of accumulation, one rounding)."""
+    x = wl.fused_inputs("t", "bf16", B, H, N, 64, seed=4300 + N, scale=scale, row_factor=(0.5, 2.0))
+    S = gu.run_scores(x, guard=8192)
+    _check_scores(x, S, f"scores of short sequences {B}x{H}x{N}")
+    monkeypatch.setenv("ATTNW_FUSED_KERNEL", "twopass")
+    S2 = gu.run_scores(x, guard=8192)
+    assert torch.equal(S.view(torch.int16), S2.view(torch.int16))

@@ -102,8 +102,8 @@ def test_rows_on_16_byte_boundaries_take_whole_line_stores(B, H, N, d, what):
     _ring_case(B, H, N, d, what)
 
 
-def _ring_case(B, H, N, d, what):
-    x = wl.fused_inputs("t", "bf16", B, H, N, d, seed=1700 + N + d, row_factor=(0.5, 2.0))
+def _ring_case(B, H, N, d, what, scale=None):
+    x = wl.fused_inputs("t", "bf16", B, H, N, d, seed=1700 + N + d, scale=scale, row_factor=(0.5, 2.0))
     heads = sorted({0, 1, B * H // 2, B * H - 1})
     Qf, Kf = x.Q.reshape(B * H, N, d), x.K.reshape(B * H, N, d)
     if what == "fused":
@@ -119,6 +119,19 @@ def _ring_case(B, H, N, d, what):
             ref = oracle.scores(Qf[bh], Kf[bh], "bf16", x.scale)
             acc = d * 2.0 ** -24 * abs(float(x.scale)) * (np.abs(wl.widen(Qf[bh], "bf16")) @ np.abs(wl.widen(Kf[bh], "bf16")).T)
             assert (np.abs(got[bh] - ref) <= acc + 2.0 ** -8 * np.abs(ref) + 1e-30).all(), f"ring scores head {bh}"
+
+
+# the last, partial strip as a launch of its own (32-query strips, keys over the 8 waves) where its workgroups would
+# start another round on the chip's 256 compute units: 8, 1, 41 and 90 queries in it (1, 1, 2, 3 strips of the second
+# launch), 128-query strips: 1 and 65
+@pytest.mark.parametrize("B,H,N,d,scale", [(1, 16, 4104, 128, None), (1, 16, 4097, 64, -0.2), (1, 32, 2089, 128, None),
+                                           (1, 51, 1370, 64, None), (1, 128, 513, 32, None), (1, 73, 961, 64, -0.1)])
+@pytest.mark.parametrize("what", ["fused", "scores"])
+def test_last_strip_of_a_ragged_length_as_a_launch_of_its_own(B, H, N, d, scale, what):
+    BM = 256 if N >= (704 if N % 2 else 1280) and not (N % 2 and N < 1152 and d <= 64) else 128
+    full, slots = B * H * (N // BM), 256 * (1 if BM == 256 else 2)
+    assert 0 < N % BM <= 96 and -(-full // slots) < -(-(full + B * H) // slots)
+    _ring_case(B, H, N, d, what, scale=scale)
 
 
 @pytest.mark.parametrize("B,H,N,d", [(4, 50, 577, 64), (2, 60, 333, 32), (1, 100, 1001, 64), (3, 70, 321, 48), (1, 40, 1151, 16)])
