@@ -365,7 +365,9 @@ SHAPES_QK = [("bf16", 1, 1, 1024, 128), ("bf16", 1, 1, 2048, 128), ("bf16", 1, 1
              ("bf16", 1, 16, 4000, 128), ("bf16", 1, 16, 4072, 128), ("bf16", 1, 16, 4104, 128), ("bf16", 1, 16, 4097, 128),
              ("bf16", 1, 16, 2056, 128), ("bf16", 1, 16, 3968, 64), ("bf16", 4, 16, 2049, 64), ("bf16", 8, 16, 1025, 64),
              ("bf16", 16, 12, 577, 64), ("bf16", 16, 12, 576, 64),
-             ("bf16", 8, 16, 640, 64), ("bf16", 64, 16, 128, 64), ("bf16", 64, 16, 197, 64), ("f32", 1, 16, 2048, 64),
+             ("bf16", 8, 16, 640, 64), ("bf16", 64, 16, 128, 64), ("bf16", 64, 16, 197, 64),
+             ("bf16", 4096, 3, 49, 32), ("bf16", 1024, 4, 64, 32), ("bf16", 64, 16, 100, 64), ("bf16", 64, 12, 64, 64),
+             ("f32", 1, 16, 2048, 64),
              ("f32", 1, 16, 4000, 64)]
 SHAPES_ATTENTION = [("bf16", 1, 16, 4096, 128), ("bf16", 1, 16, 4096, 64), ("bf16", 1, 32, 4096, 32), ("bf16", 1, 16, 4000, 128),
                     ("bf16", 1, 40, 2100, 64), ("bf16", 8, 16, 512, 64), ("bf16", 64, 16, 197, 64), ("bf16", 1, 2, 32768, 128),

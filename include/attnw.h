@@ -40,7 +40,9 @@
  *   - Environment: ATTNW_FUSED_KERNEL selects among the kernels behind
  *     attnw_fused / attnw_gemm_scores for bf16 shapes that several of them
  *     serve (read at every call; tests and measurements compare them):
- *       unset    d = 64 and N = 512 or 1024, or N up to 608 and not a multiple
+ *       unset    N from 8 to 128 (d up to 128; not N above 96 with d above 96):
+ *                a wave per head and 32 queries, scores in its registers;
+ *                d = 64 and N = 512 or 1024, or N up to 608 and not a multiple
  *                of 32: scores of a strip held in registers, one sweep; one
  *                to a few heads of 1024 to 8192 keys: scores held across a
  *                gang of workgroups; else N a multiple of 256 and d = 64 or
@@ -48,6 +50,7 @@
  *       rounds   never the register-resident kernels
  *       twopass  always the general two-pass kernel
  *       gang     the gang kernel wherever it takes the shape
+ *       tiny     the wave-per-head kernel wherever it takes the shape
  *     Weights of all of them agree to rounding of the row sum, scores bit for bit.
  */
 #ifndef ATTNW_H

@@ -40,6 +40,12 @@ bool qk_flat_supported(int64_t BH, int64_t N, int64_t d);
 hipError_t launch_qk_flat(bool scores_only, const void* Q, const void* K, void* out, int64_t BH, int64_t N, float scale,
                           hipStream_t stream);
 
+// Fused attention weights or scaled scores, bf16, N <= 128, d a multiple of 16 up to 128, many heads: a wave per
+// (head, 32 queries) with the K of the head as matrix operands in its registers, no LDS but the way out, no barriers.
+bool qk_tiny_supported(int64_t BH, int64_t N, int64_t d);
+hipError_t launch_qk_tiny(bool scores_only, const void* Q, const void* K, void* out, int64_t BH, int64_t N, int64_t d,
+                          float scale, hipStream_t stream);
+
 // Fused attention weights, bf16, d = 64 or 128, N a multiple of 512 from 1024 to 16384: the scores of a strip stay
 // in the registers of the N / 512 workgroups that share its rows (one sweep over the keys; the workgroups exchange
 // their row statistics through tables parked in P).  Two launches: table slots zeroed, then the kernel.

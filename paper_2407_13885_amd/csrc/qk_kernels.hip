@@ -805,6 +805,18 @@ hipError_t launch_qk(DType dt, bool scores_only, const void* Q, const void* K, v
     const bool twopass = force && strcmp(force, "twopass") == 0;
     const bool rounds = force && strcmp(force, "rounds") == 0;
     const bool gang = force && strcmp(force, "gang") == 0;
+    const bool tiny = force && strcmp(force, "tiny") == 0;
+    // Sequences of up to 128 tokens: the kernel in which a wave works alone on a (head, 32 queries) pair.  Measured
+    // against the kernels below, fused / scores in us: 12288 heads of N = 49, d = 32 320 / 219 -> 27 / 26; 4096 heads of
+    // N = 64, d = 32 69 / 35 -> 10 / 10; 1024 heads of d = 64: N = 33 14 / 11 -> 6 / 5.5, 64 20 / 12 -> 6 / 6, 100 22 / 17 -> 16 / 15,
+    // 128 25 / 17 -> 18 / 17; 16 heads: N = 49, d = 32 8.9 / 6.3 -> 4.3 / 4.2, N = 127, d = 96 12.6 / 9.3 -> 6.8 / 6.1.  Not taken:
+    // N = 128 with fewer than 512 (head, 32 queries) pairs (64 heads of d = 64: 5.4 / 3.8 against 5.7 / 5.1), scores of
+    // lengths that are multiples of 32 with fewer than 2048 pairs (256 heads of N = 128: 5.4 against 6.0).
+    if (qk_tiny_supported(BH, N, d)) {
+        const int64_t units = BH * ((N + 31) / 32);
+        const bool take = scores_only ? ((N % 32) != 0 || units >= 2048) : !(N == 128 && units < 512);
+        if (tiny || (!force && take)) return launch_qk_tiny(scores_only, Q, K, out, BH, N, d, scale, stream);
+    }
     // Short sequences whose length is not a multiple of 32 (d = 64; 197, 257, 577 ...): the kernel that stages a strip
     // as the contiguous block of P that it is.  Measured against the general kernel, us: B64 H16 N = 33 31 -> 14,
     // 65 34 -> 20, 100 26 -> 21, 161 66 -> 40, 197 74 -> 50, 200 50 -> 41; B32 H12 N = 257 75 -> 46, 300 52 -> 43; B16 H12
