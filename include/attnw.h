@@ -42,8 +42,9 @@
  *     serve (read at every call; tests and measurements compare them):
  *       unset    N from 8 to 128 (d up to 128; not N above 96 with d above 96):
  *                a wave per head and 32 queries, scores in its registers;
- *                d = 64 and N = 512 or 1024, or N up to 608 and not a multiple
- *                of 32: scores of a strip held in registers, one sweep; one
+ *                d = 64 and N = 512 or 1024, or d = 32 or 64 and N up to 608
+ *                and not a multiple of 32: scores of a strip held in registers,
+ *                one sweep; one
  *                to a few heads of 1024 to 8192 keys: scores held across a
  *                gang of workgroups; else N a multiple of 256 and d = 64 or
  *                128 (scores: d = 64): round-based kernel; else general kernel

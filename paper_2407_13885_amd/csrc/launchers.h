@@ -32,13 +32,13 @@ bool qk_resident_supported(int64_t BH, int64_t N, int64_t d);
 hipError_t launch_qk_resident(const void* Q, const void* K, void* out, int64_t BH, int64_t N, float scale,
                               hipStream_t stream);
 
-// Fused attention weights or scaled scores, bf16, d = 64, any N up to 608 (the odd lengths of a class token in front of a
-// patch grid):
+// Fused attention weights or scaled scores, bf16, d = 32 or 64, any N up to 608 (the odd lengths of a class token in
+// front of a patch grid):
 // scores of a 32-query strip resident in registers, the strip staged as the contiguous block of P that it is and
 // written as aligned 16-byte chunks.
 bool qk_flat_supported(int64_t BH, int64_t N, int64_t d);
-hipError_t launch_qk_flat(bool scores_only, const void* Q, const void* K, void* out, int64_t BH, int64_t N, float scale,
-                          hipStream_t stream);
+hipError_t launch_qk_flat(bool scores_only, const void* Q, const void* K, void* out, int64_t BH, int64_t N, int64_t d,
+                          float scale, hipStream_t stream);
 
 // Fused attention weights or scaled scores, bf16, N <= 128, d a multiple of 16 up to 128, many heads: a wave per
 // (head, 32 queries) with the K of the head as matrix operands in its registers, no LDS but the way out, no barriers.

@@ -1,4 +1,4 @@
-// Fused attention weights  P = softmax(scale * Q K^T)  for SHORT sequences of ANY length (bf16, d = 64, N <= 608):
+// Fused attention weights  P = softmax(scale * Q K^T)  for SHORT sequences of ANY length (bf16, d = 32 or 64, N <= 608):
 // the lengths of a class token in front of a patch grid -- 197, 257, 577 -- are odd, so no row of P but the
 // first starts on a 16-byte boundary, and a kernel that stores pieces of rows is left with 2-byte stores.
 //
@@ -37,12 +37,13 @@ constexpr int kFlatMaxN = 608;                    // 256 N bytes of LDS: K of a 
 // statistics buffers, two block buffers.
 // SCORES: write scale * Q K^T instead of the weights (the first stage of the unfused pipelines: no statistics, the same
 //         way out); c is then the scale itself
-template <int NT, int GRAN, bool SCORES>
+// DB: bytes of a row of Q or K (64, 128: d = 32, 64)
+template <int DB, int NT, int GRAN, bool SCORES>
 __global__ __launch_bounds__(512)
 void qk_flat_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, uint16_t* __restrict__ out, int N,
                     float c, uint32_t sign_flip, uint32_t strips_per_head, uint32_t total_strips)
 {
-    constexpr int NW = 8, DB = 128, G = DB / 32, CPR = DB / 16, NTHREADS = 64 * NW;
+    constexpr int NW = 8, G = DB / 32, CPR = DB / 16, NTHREADS = 64 * NW;
     constexpr int KEYS = 32 * NT * NW;            // keys the waves cover
     constexpr int K_ROWS = KEYS < kFlatMaxN ? KEYS : kFlatMaxN;
     constexpr int K_BYTES = K_ROWS * DB;
@@ -262,7 +263,7 @@ void qk_flat_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict__
     }
 }
 
-template <int NT, int GRAN>
+template <int DB, int NT, int GRAN>
 hipError_t launch_flat_t(bool scores_only, const void* Q, const void* K, void* out, int64_t BH, int N, float scale, hipStream_t stream)
 {
     const uint32_t strips_per_head = (uint32_t)((N + 31) / 32);
@@ -276,36 +277,45 @@ hipError_t launch_flat_t(bool scores_only, const void* Q, const void* K, void* o
     const float c = scores_only ? scale : fabsf(scale) * kLog2e;
     const uint32_t flip = (!scores_only && scale < 0.0f) ? Mma<uint16_t>::kSignMask : 0u;
     if (scores_only)
-        hipLaunchKernelGGL((qk_flat_kernel<NT, GRAN, true>), dim3(grid), dim3(512), 0, stream, static_cast<const uint16_t*>(Q),
+        hipLaunchKernelGGL((qk_flat_kernel<DB, NT, GRAN, true>), dim3(grid), dim3(512), 0, stream, static_cast<const uint16_t*>(Q),
                            static_cast<const uint16_t*>(K), static_cast<uint16_t*>(out), N, c, flip, strips_per_head, total);
     else
-        hipLaunchKernelGGL((qk_flat_kernel<NT, GRAN, false>), dim3(grid), dim3(512), 0, stream, static_cast<const uint16_t*>(Q),
+        hipLaunchKernelGGL((qk_flat_kernel<DB, NT, GRAN, false>), dim3(grid), dim3(512), 0, stream, static_cast<const uint16_t*>(Q),
                            static_cast<const uint16_t*>(K), static_cast<uint16_t*>(out), N, c, flip, strips_per_head, total);
     return hipGetLastError();
 }
 
-template <int NT>
+template <int DB, int NT>
 hipError_t launch_flat(bool scores_only, const void* Q, const void* K, void* out, int64_t BH, int N, float scale, hipStream_t stream)
 {
-    if (N % 4 == 0) return launch_flat_t<NT, 8>(scores_only, Q, K, out, BH, N, scale, stream);
-    if (N % 2 == 0) return launch_flat_t<NT, 4>(scores_only, Q, K, out, BH, N, scale, stream);
-    return launch_flat_t<NT, 2>(scores_only, Q, K, out, BH, N, scale, stream);
+    if (N % 4 == 0) return launch_flat_t<DB, NT, 8>(scores_only, Q, K, out, BH, N, scale, stream);
+    if (N % 2 == 0) return launch_flat_t<DB, NT, 4>(scores_only, Q, K, out, BH, N, scale, stream);
+    return launch_flat_t<DB, NT, 2>(scores_only, Q, K, out, BH, N, scale, stream);
+}
+
+template <int DB>
+hipError_t launch_flat_d(bool scores_only, const void* Q, const void* K, void* out, int64_t BH, int N, float scale, hipStream_t stream)
+{
+    if (N <= 256) return launch_flat<DB, 1>(scores_only, Q, K, out, BH, N, scale, stream);
+    if (N <= 512) return launch_flat<DB, 2>(scores_only, Q, K, out, BH, N, scale, stream);
+    return launch_flat<DB, 3>(scores_only, Q, K, out, BH, N, scale, stream);
 }
 
 }  // namespace
 
 bool qk_flat_supported(int64_t BH, int64_t N, int64_t d)
 {
-    if (d != 64 || N < 1 || N > kFlatMaxN) return false;
+    // (d = 128 measured slower than the general kernel: K of a head and two blocks leave room for one workgroup per
+    // compute unit -- 1024 heads of N = 197 91 -> 99 us, of N = 255 95 -> 125)
+    if ((d != 32 && d != 64) || N < 1 || N > kFlatMaxN) return false;
     return BH * ((N + 31) / 32) <= (int64_t)0x7ffffff0;
 }
 
-hipError_t launch_qk_flat(bool scores_only, const void* Q, const void* K, void* out, int64_t BH, int64_t N, float scale,
-                          hipStream_t stream)
+hipError_t launch_qk_flat(bool scores_only, const void* Q, const void* K, void* out, int64_t BH, int64_t N, int64_t d,
+                          float scale, hipStream_t stream)
 {
-    if (N <= 256) return launch_flat<1>(scores_only, Q, K, out, BH, (int)N, scale, stream);
-    if (N <= 512) return launch_flat<2>(scores_only, Q, K, out, BH, (int)N, scale, stream);
-    return launch_flat<3>(scores_only, Q, K, out, BH, (int)N, scale, stream);
+    if (d == 32) return launch_flat_d<64>(scores_only, Q, K, out, BH, (int)N, scale, stream);
+    return launch_flat_d<128>(scores_only, Q, K, out, BH, (int)N, scale, stream);
 }
 
 }  // namespace attnw

@@ -825,7 +825,7 @@ hipError_t launch_qk(DType dt, bool scores_only, const void* Q, const void* K, v
     // against 64).
     // (scores of even lengths leave the general kernel as fast: its 4-byte stores pair up; measured 100 <= N <= 584)
     if (!force && (N % 32) != 0 && (!scores_only || (N & 1)) && qk_flat_supported(BH, N, d))
-        return launch_qk_flat(scores_only, Q, K, out, BH, N, scale, stream);
+        return launch_qk_flat(scores_only, Q, K, out, BH, N, d, scale, stream);
     if (!scores_only && qk_gang_supported(BH, N, d) && (gang || (!force && prefers_gang(BH, N, d))))
         return launch_qk_gang(Q, K, out, BH, N, d, scale, stream);
     if (!twopass && !(!rounds && prefers_key_split(BH, N, d))) {

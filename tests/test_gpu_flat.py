@@ -20,10 +20,10 @@ def _gpu():
     gu.require_gpu()
 
 
-def _check(B, H, N, scale=None, row_factor=(0.5, 2.0), seed=0):
-    x = wl.fused_inputs("t", "bf16", B, H, N, 64, seed=4100 + N + seed, scale=scale, row_factor=row_factor)
+def _check(B, H, N, scale=None, row_factor=(0.5, 2.0), seed=0, d=64):
+    x = wl.fused_inputs("t", "bf16", B, H, N, d, seed=4100 + N + seed, scale=scale, row_factor=row_factor)
     got = gu.to_f64(gu.run_fused(x, guard=8192)).reshape(B * H, N, N)
-    Qf, Kf = x.Q.reshape(B * H, N, 64), x.K.reshape(B * H, N, 64)
+    Qf, Kf = x.Q.reshape(B * H, N, d), x.K.reshape(B * H, N, d)
     for bh in sorted({0, 1 % (B * H), B * H // 2, B * H - 1}):
         ref = oracle.attention_weights(Qf[bh], Kf[bh], "bf16", x.scale)
         gu.check_weights(got[bh], ref, "bf16", f"short sequence {B}x{H}x{N} head {bh}")
@@ -37,6 +37,14 @@ def _check(B, H, N, scale=None, row_factor=(0.5, 2.0), seed=0):
                                601, 607])
 def test_short_sequences_any_length(N):
     _check(1, 3, N)
+
+
+@pytest.mark.parametrize("N", [129, 144, 197, 255, 257, 333, 510, 577, 607])
+def test_short_sequences_of_32_element_heads(N):
+    """d = 32: rows of 64 bytes, four K rows per 256-byte line of LDS."""
+    _check(1, 3, N, d=32, seed=3)
+    if N in (144, 197):
+        _check(2, 150, N, d=32, seed=4)
 
 
 @pytest.mark.parametrize("B,H,N", [(4, 70, 197), (2, 150, 257), (1, 300, 65), (3, 40, 577), (1, 9, 601)])
@@ -61,25 +69,31 @@ def test_the_general_kernel_still_serves_these_lengths(N, monkeypatch):
 
 
 def _check_scores(x, S, what):
+    d = x.Q.shape[-1]
     got = gu.to_f64(S)
     Qa, Ka = np.abs(wl.widen(x.Q, "bf16")), np.abs(wl.widen(x.K, "bf16"))
     B, H = x.Q.shape[:2]
     for b in range(B):
         for h in range(H):
             ref = oracle.scores(x.Q[b, h], x.K[b, h], "bf16", x.scale)
-            acc_bound = 64 * 2.0 ** -24 * abs(float(x.scale)) * (Qa[b, h] @ Ka[b, h].T)
+            acc_bound = d * 2.0 ** -24 * abs(float(x.scale)) * (Qa[b, h] @ Ka[b, h].T)
             assert (np.abs(got[b, h] - ref) <= acc_bound + 2.0 ** -8 * np.abs(ref) + 1e-30).all(), f"{what} head {b},{h}"
 
 
 @pytest.mark.parametrize("B,H,N,scale", [(1, 3, 1, None), (1, 3, 33, None), (2, 70, 197, None), (1, 3, 198, -0.37),
                                          (1, 2, 200, 1.0), (1, 150, 257, None), (1, 3, 333, 0.0), (2, 20, 577, None),
                                          (1, 3, 578, None), (1, 3, 607, -1.0)])
-def test_scaled_scores_of_short_sequences(B, H, N, scale, monkeypatch):
+def test_scaled_scores_of_short_sequences(B, H, N, scale, monkeypatch, d=64):
     """attnw_gemm_scores on the same lengths: the same kernel without the statistics.  Against the oracle, the
     guard bands around S, and bit for bit against the general kernel (same order of accumulation, one rounding)."""
-    x = wl.fused_inputs("t", "bf16", B, H, N, 64, seed=4300 + N, scale=scale, row_factor=(0.5, 2.0))
+    x = wl.fused_inputs("t", "bf16", B, H, N, d, seed=4300 + N, scale=scale, row_factor=(0.5, 2.0))
     S = gu.run_scores(x, guard=8192)
     _check_scores(x, S, f"scores of short sequences {B}x{H}x{N}")
     monkeypatch.setenv("ATTNW_FUSED_KERNEL", "twopass")
     S2 = gu.run_scores(x, guard=8192)
     assert torch.equal(S.view(torch.int16), S2.view(torch.int16))
+
+
+@pytest.mark.parametrize("N", [145, 333, 577])
+def test_scaled_scores_of_32_element_heads(N, monkeypatch):
+    test_scaled_scores_of_short_sequences(1, 3, N, None, monkeypatch, d=32)
