@@ -4,6 +4,9 @@
 #include "attnw.h"
 #include "launchers.h"
 
+#include <cstdlib>
+#include <cstring>
+
 #include <limits>
 
 namespace {
@@ -93,6 +96,13 @@ int attnw_attention(const void* Q, const void* K, const void* V, void* O, int64_
     if (overlaps(O, bytes, Q, bytes) || overlaps(O, bytes, K, bytes) || overlaps(O, bytes, V, bytes))
         return ATTNW_ERR_ALIAS;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    // many short sequences: the kernel in which a wave works alone on a (head, 32 queries) pair
+    // (ATTNW_ATTENTION_KERNEL=tiny puts every shape it takes on it, =tiled none: tests and measurements compare them)
+    if (dtype == ATTNW_BF16 && attnw::attention_tiny_supported(BH, N, d)) {
+        const char* force = getenv("ATTNW_ATTENTION_KERNEL");
+        const bool want = force ? strcmp(force, "tiny") == 0 : attnw::prefers_attention_tiny(BH, N, d);
+        if (want) return attnw::launch_attention_tiny(Q, K, V, O, BH, N, d, scale, st) == hipSuccess ? ATTNW_OK : ATTNW_ERR_LAUNCH;
+    }
     const hipError_t e = tiled ? attnw::launch_attention(Q, K, V, O, BH, N, d, scale, st)
                                : attnw::launch_attention_general(dt, Q, K, V, O, BH, N, d, scale, st);
     return e == hipSuccess ? ATTNW_OK : ATTNW_ERR_LAUNCH;
