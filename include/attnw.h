@@ -35,13 +35,16 @@
  *     base pointer, overlap of output with inputs.
  *   - Inputs must be finite.  A NaN poisons its own row only.
  *   - The library keeps no mutable global state apart from a per-device cache
- *     of the compute-unit count; calls from several host threads on different
+ *     of the compute-unit count and, per kernel for short sequences, of the
+ *     number of its workgroups that a compute unit holds (queried once, at the
+ *     first call that needs it); calls from several host threads on different
  *     streams are safe.
  *   - Environment: ATTNW_FUSED_KERNEL selects among the kernels behind
  *     attnw_fused / attnw_gemm_scores for bf16 shapes that several of them
  *     serve (read at every call; tests and measurements compare them):
- *       unset    N from 8 to 128 (d up to 128; not N above 96 with d above 96):
- *                a wave per head and 32 queries, scores in its registers;
+ *       unset    N from 8 to 128 (d up to 128; not N above 96 with d above 96)
+ *                or to 192 (d up to 64): a wave per head and 32 queries, scores
+ *                in its registers;
  *                d = 64 and N = 512 or 1024, or d = 32 or 64 and N up to 608
  *                and not a multiple of 32: scores of a strip held in registers,
  *                one sweep; one

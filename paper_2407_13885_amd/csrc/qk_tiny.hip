@@ -1,5 +1,5 @@
-// Fused attention weights  P = softmax(scale * Q K^T)  and scaled scores for MANY SHORT sequences (bf16, N <= 128,
-// d a multiple of 16 up to 128): windows of 49 or 64 tokens with three to thirty-two heads each and thousands of
+// Fused attention weights  P = softmax(scale * Q K^T)  and scaled scores for MANY SHORT sequences (bf16, N <= 128 with
+// d a multiple of 16 up to 128, N <= 256 with d <= 64): windows of 49 or 64 tokens with three to thirty-two heads each and thousands of
 // windows per call, sentences of up to 128 tokens.  One head is a few matrix instructions of work; a workgroup
 // per (head, strip) spends its time in prologue and barriers, and of eight waves that split 256 keys only two
 // have any.
@@ -56,6 +56,7 @@ void qk_tiny_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict__
     constexpr int BLK_ELEMS = 32 * 32 * NKB + 32 * 8;   // as in memory: 7 + 32 N; row by row: 32 (N + 8)
     constexpr int NST = 2 * NKB;                  // store instructions per unit: 64 chunks each, (7 + 32 * 32 NKB) / 8 at most
     constexpr int LAST = NKB - 1;                 // the block of keys that N may cut (32 LAST < N <= 32 NKB)
+    constexpr bool LATE = NKB > 4;                // where in a unit the operands of the next one are requested
     __shared__ __align__(16) uint16_t blk_lds[kTinyWaves][BLK_ELEMS];
     __shared__ __align__(16) uint16_t lead_lds[kTinyWaves][8];
     __shared__ __align__(16) uint16_t dump_lds[kTinyWaves][40];   // where the keys past N of a block go (32 + a run of 4)
@@ -138,7 +139,7 @@ void qk_tiny_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict__
             qb1 = 0;
             ++h1;
         }
-        request(h1, qb1);
+        if constexpr (!LATE) request(h1, qb1);
 
         // ---- row statistics and weights in place (Eq. 1) ---------------------------------------------------------------
         float inv = c;                            // SCORES: the scale
@@ -221,6 +222,9 @@ void qk_tiny_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict__
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        // (more than four blocks of keys: the scores and the K operands together exceed the registers, so the request
+        // waits until the scores have left them -- still ahead of this unit's stores)
+        if constexpr (LATE) request(h1, qb1);
 
         // ---- whole chunks leave: NST store instructions whatever the length ----------------------------------------------
         const int staged = o + rows * N;          // elements in the area (rows16: o = 0, a multiple of 8)
@@ -318,9 +322,9 @@ hipError_t launch_tiny(bool scores_only, const void* Q, const void* K, void* out
     case 1: return launch_tiny_t<NKB, 1>(scores_only, Q, K, out, BH, N, scale, stream);
     case 2: return launch_tiny_t<NKB, 2>(scores_only, Q, K, out, BH, N, scale, stream);
     case 3: return launch_tiny_t<NKB, 3>(scores_only, Q, K, out, BH, N, scale, stream);
-    case 4: return launch_tiny_t<NKB, 4>(scores_only, Q, K, out, BH, N, scale, stream);
-    case 5: return launch_tiny_t<NKB, 5>(scores_only, Q, K, out, BH, N, scale, stream);
-    case 6: return launch_tiny_t<NKB, 6>(scores_only, Q, K, out, BH, N, scale, stream);
+    case 4: if constexpr (NKB <= 7) return launch_tiny_t<NKB, 4>(scores_only, Q, K, out, BH, N, scale, stream); else break;
+    case 5: if constexpr (NKB <= 4) return launch_tiny_t<NKB, 5>(scores_only, Q, K, out, BH, N, scale, stream); else break;
+    case 6: if constexpr (NKB <= 4) return launch_tiny_t<NKB, 6>(scores_only, Q, K, out, BH, N, scale, stream); else break;
     case 7: if constexpr (NKB < 4) return launch_tiny_t<NKB, 7>(scores_only, Q, K, out, BH, N, scale, stream); else break;
     case 8: if constexpr (NKB < 4) return launch_tiny_t<NKB, 8>(scores_only, Q, K, out, BH, N, scale, stream); else break;
     default: break;
@@ -332,8 +336,10 @@ hipError_t launch_tiny(bool scores_only, const void* Q, const void* K, void* out
 
 bool qk_tiny_supported(int64_t BH, int64_t N, int64_t d)
 {
-    if (N < 8 || N > 128 || d < 16 || d > 128 || (d % 16) != 0) return false;   // (N >= 8: see the stores of a unit)
+    if (N < 8 || N > 256 || d < 16 || d > 128 || (d % 16) != 0) return false;   // (N >= 8: see the stores of a unit)
     if (N > 96 && d > 96) return false;           // (operands and scores of a unit would not fit the registers)
+    if (N > 128 && d > 64) return false;
+    if (N > 224 && d > 48) return false;
     return BH * ((N + 31) / 32) <= (int64_t)0x7ffffff0;
 }
 
@@ -343,7 +349,11 @@ hipError_t launch_qk_tiny(bool scores_only, const void* Q, const void* K, void* 
     if (N <= 32) return launch_tiny<1>(scores_only, Q, K, out, BH, (int)N, (int)d, scale, stream);
     if (N <= 64) return launch_tiny<2>(scores_only, Q, K, out, BH, (int)N, (int)d, scale, stream);
     if (N <= 96) return launch_tiny<3>(scores_only, Q, K, out, BH, (int)N, (int)d, scale, stream);
-    return launch_tiny<4>(scores_only, Q, K, out, BH, (int)N, (int)d, scale, stream);
+    if (N <= 128) return launch_tiny<4>(scores_only, Q, K, out, BH, (int)N, (int)d, scale, stream);
+    if (N <= 160) return launch_tiny<5>(scores_only, Q, K, out, BH, (int)N, (int)d, scale, stream);
+    if (N <= 192) return launch_tiny<6>(scores_only, Q, K, out, BH, (int)N, (int)d, scale, stream);
+    if (N <= 224) return launch_tiny<7>(scores_only, Q, K, out, BH, (int)N, (int)d, scale, stream);
+    return launch_tiny<8>(scores_only, Q, K, out, BH, (int)N, (int)d, scale, stream);
 }
 
 }  // namespace attnw

@@ -225,3 +225,53 @@ def test_split_key_fused_in_a_captured_graph():
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(P.view(torch.int16), want), f"replay {rep}"
+
+
+def _captured_replays_match_eager(call, out, replays=3):
+    """`call(stream)` enqueues the library call that writes `out`.  Eager once, then recorded by a stream capture;
+    every replay must give the eager bits whatever `out` held before."""
+    call(torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    want = out.view(torch.int16).clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        call(side)
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            call(torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    for rep in range(replays):
+        out.fill_(float(rep) * 7.0 - 3.0)                 # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), want), f"replay {rep}"
+
+
+def test_last_strip_launch_of_a_ragged_length_in_a_captured_graph():
+    """32 heads of 2089 keys: the 41 queries past the last full 256-query strip are a second launch."""
+    B, H, N, d = 1, 32, 2089, 128
+    x = wl.fused_inputs("t", "bf16", B, H, N, d, seed=2400)
+    Q, K = gu.to_dev(x.Q, "bf16"), gu.to_dev(x.K, "bf16")
+    P = torch.empty((B, H, N, N), dtype=torch.bfloat16, device="cuda")
+    _captured_replays_match_eager(lambda s: attnw.attnw_fused(Q, K, P, B, H, N, d, float(x.scale), attnw.ATTNW_BF16, s), P)
+
+
+@pytest.mark.parametrize("what", ["fused", "scores", "attention"])
+def test_many_short_sequences_in_a_captured_graph(what):
+    """The kernels in which a wave works alone on a (head, 32 queries) pair (their grid comes from an occupancy query
+    made once per process, at the first call)."""
+    B, H, N, d = 300, 4, 49, 32
+    x = wl.fused_inputs("t", "bf16", B, H, N, d, seed=2500)
+    Q, K = gu.to_dev(x.Q, "bf16"), gu.to_dev(x.K, "bf16")
+    sc = float(x.scale)
+    if what == "attention":
+        V = gu.to_dev(wl.value_inputs(x, seed=2501), "bf16")
+        O = torch.empty((B, H, N, d), dtype=torch.bfloat16, device="cuda")
+        _captured_replays_match_eager(lambda s: attnw.attnw_attention(Q, K, V, O, B, H, N, d, sc, attnw.ATTNW_BF16, s), O)
+    else:
+        fn = attnw.attnw_fused if what == "fused" else attnw.attnw_gemm_scores
+        P = torch.empty((B, H, N, N), dtype=torch.bfloat16, device="cuda")
+        _captured_replays_match_eager(lambda s: fn(Q, K, P, B, H, N, d, sc, attnw.ATTNW_BF16, s), P)

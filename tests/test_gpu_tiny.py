@@ -1,5 +1,5 @@
-"""GPU parity of attnw_fused / attnw_gemm_scores on many short sequences (bf16, N <= 128, d a multiple of 16 up to
-128: the kernel in which a wave works alone on a (head, 32 queries) pair) against the fp64 oracle: every element of
+"""GPU parity of attnw_fused / attnw_gemm_scores on many short sequences (bf16, N <= 128 with d a multiple of 16 up to
+128, N <= 256 with d <= 64: the kernel in which a wave works alone on a (head, 32 queries) pair) against the fp64 oracle: every element of
 sampled heads at the bf16 bar, every row sum, the guard bands around the output, the scores bit for bit against the
 general kernel."""
 import numpy as np
@@ -66,8 +66,29 @@ def test_every_head_size(N, d, monkeypatch):
     _check_fused(1, 6, N, d, seed=1)
 
 
+# five to eight blocks of keys (the operands of the next unit are requested later in a unit): every way a length meets
+# blocks, chunks and staging writes again; d = 64 up to 224 keys, d <= 48 up to 256
+@pytest.mark.parametrize("N,d", [(129, 64), (136, 64), (144, 32), (150, 64), (159, 16), (160, 64), (161, 32), (176, 48), (191, 64),
+                                 (192, 64), (193, 32), (197, 64), (200, 32), (223, 64), (224, 64), (225, 32), (250, 48), (255, 32),
+                                 (256, 32), (256, 16)])
+def test_lengths_up_to_256(N, d, monkeypatch):
+    monkeypatch.setenv("ATTNW_FUSED_KERNEL", "tiny")
+    _check_fused(1, 5, N, d, seed=3)
+    if N in (144, 160, 197, 256):
+        _check_fused(2, 300, N, d, seed=4)        # more units than resident waves
+
+
+@pytest.mark.parametrize("N,d", [(129, 64), (145, 32), (160, 64), (197, 64), (256, 32)])
+def test_scaled_scores_up_to_256(N, d, monkeypatch):
+    monkeypatch.setenv("ATTNW_FUSED_KERNEL", "tiny")
+    x, S = _check_scores(2, 40, N, d, seed=5)
+    monkeypatch.setenv("ATTNW_FUSED_KERNEL", "twopass")
+    S2 = gu.run_scores(x, guard=8192)
+    assert torch.equal(S.view(torch.int16), S2.view(torch.int16))
+
+
 @pytest.mark.parametrize("B,H,N,d", [(100, 7, 49, 32), (1000, 3, 49, 32), (4096, 3, 49, 32), (500, 4, 100, 64), (64, 16, 128, 64),
-                                     (300, 3, 64, 32), (40, 16, 128, 128), (2000, 1, 33, 16), (90, 12, 77, 64)])
+                                     (300, 3, 64, 32), (40, 16, 128, 128), (2000, 1, 33, 16), (90, 12, 77, 64), (30, 12, 160, 64), (64, 12, 144, 32)])
 def test_many_heads_by_default(B, H, N, d):
     """The shapes that take this kernel without being asked: at least 512 (head, 32-query) units.  More units than
     resident waves: unit ranges that cross head boundaries (the K operands of the next head replace the ones in
