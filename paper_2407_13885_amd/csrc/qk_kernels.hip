@@ -676,8 +676,9 @@ hipError_t launch_ring_t(bool scores_only, const void* Q, const void* K, void* o
     // time of a full workgroup.  Where those workgroups make the difference between one more round of workgroups
     // on the chip and none (N = 4104, 16 heads: 272 workgroups of 256-query strips on 256 compute units), the last
     // strip becomes a launch of its own: 32-query strips whose keys are spread over the 8 waves of a workgroup.
-    // Measured, fused / scores in us, B1 H16 d = 128: N = 4104 296 / 226 -> 260 / 150, 4097 322 / 201 -> 266 / 169, 4100
-    // 294 / 175 -> 238 / 144, 8200 929 -> 866 (4072, 16 full strips and nothing else: 203 - 210 / 131).
+    // Measured, fused / scores in us, B1 H16 d = 128: N = 4104 296 / 226 -> 251 / 141, 4097 322 / 201 -> 266 / 156, 4100
+    // 294 / 175 -> 222 / 139, 8200 929 -> 830 (4072, 16 full strips and nothing else: 203 - 210 / 131); 128 heads of N = 513,
+    // d = 32: 53 -> 39.
     const int tail_rows = N % BM;
     const int64_t slots = (int64_t)compute_units() * (WQ == 8 ? 1 : 2);
     const int64_t full = BH * (int64_t)(N / BM);
@@ -693,16 +694,32 @@ hipError_t launch_ring_t(bool scores_only, const void* Q, const void* K, void* o
         hipLaunchKernelGGL((qk_kernel<uint16_t, DB, 1, WQ, 1, 4, false, false, 0, GRAN>), dim3(grid), dim3(64 * WQ), 0, stream,
                            q, k, o, N, d, c, flip, strips, (uint32_t)total, 1, 0);
     if (own_tail) {
+        // 32-query strips, the 128 keys of a tile over 4 waves; with so few strips their keys are split over workgroups as
+        // for problems of a few heads (SPLIT in qk_kernel: statistics through tables in P, then the weights; rows of P
+        // must start on 4-byte boundaries for the tables)
         const uint32_t tail_strips = (uint32_t)((tail_rows + 31) / 32);
-        const uint64_t tail_total = (uint64_t)BH * tail_strips;
-        const uint32_t tail_grid = (uint32_t)((tail_total + 7) / 8 * 8);
         const int q_base = (int)strips * BM;
-        if (scores_only)
+        const bool tables_fit = scores_only || (N % 2) == 0;
+        const int kc = tables_fit ? key_ranges((int64_t)BH * tail_strips, (N + 127) / 128) : 1;
+        const uint64_t tail_total = (uint64_t)BH * tail_strips * kc;
+        const uint32_t tail_grid = (uint32_t)((tail_total + 7) / 8 * 8);
+        if (kc > 1) {
+            if (scores_only) {
+                hipLaunchKernelGGL((qk_kernel<uint16_t, DB, 1, 1, 4, 1, true, false, 2>), dim3(tail_grid), dim3(256), 0, stream,
+                                   q, k, o, N, d, c, flip, tail_strips, (uint32_t)tail_total, kc, q_base);
+            } else {
+                hipLaunchKernelGGL((qk_kernel<uint16_t, DB, 1, 1, 4, 1, false, false, 1>), dim3(tail_grid), dim3(256), 0, stream,
+                                   q, k, o, N, d, c, flip, tail_strips, (uint32_t)tail_total, kc, q_base);
+                hipLaunchKernelGGL((qk_kernel<uint16_t, DB, 1, 1, 4, 1, false, false, 2>), dim3(tail_grid), dim3(256), 0, stream,
+                                   q, k, o, N, d, c, flip, tail_strips, (uint32_t)tail_total, kc, q_base);
+            }
+        } else if (scores_only) {   // (unsplit: the 256 keys of a tile over 8 waves)
             hipLaunchKernelGGL((qk_kernel<uint16_t, DB, 1, 1, 8, 1, true, false>), dim3(tail_grid), dim3(512), 0, stream,
                                q, k, o, N, d, c, flip, tail_strips, (uint32_t)tail_total, 1, q_base);
-        else
+        } else {
             hipLaunchKernelGGL((qk_kernel<uint16_t, DB, 1, 1, 8, 1, false, false>), dim3(tail_grid), dim3(512), 0, stream,
                                q, k, o, N, d, c, flip, tail_strips, (uint32_t)tail_total, 1, q_base);
+        }
     }
     return hipGetLastError();
 }
