@@ -429,10 +429,11 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
         if constexpr ((decltype(slotc)::value & 1) == 0) return acc_a; else return acc_b;
     };
 
-    // (maximum, sum) table of query q in the piece of key range k: pairs of floats at the start of the piece
-    // (accessed as single floats: a row of P starts on a 4-byte boundary at least)
+    // (maximum, sum) table of query q in the piece of key range k: pairs of floats at the first 4-byte boundary of the
+    // piece (accessed as single floats; a piece of an odd-length bf16 row may start 2 bytes before it)
     auto table_of = [&](int q, int k) __attribute__((always_inline)) {
-        return reinterpret_cast<float*>(reinterpret_cast<char*>(out_h) + ((int64_t)q * N + (int64_t)range_begin(k) * BN) * ES);
+        char* const piece = reinterpret_cast<char*>(out_h) + ((int64_t)q * N + (int64_t)range_begin(k) * BN) * ES;
+        return reinterpret_cast<float*>((reinterpret_cast<uintptr_t>(piece) + 3) & ~(uintptr_t)3);
     };
     if constexpr (SPLIT == 2 && !SCORES) {
 #pragma unroll
@@ -617,9 +618,7 @@ hipError_t launch_variant(bool scores_only, const void* Q, const void* K, void* 
     const float c = scores_only ? scale : fabsf(scale) * kLog2e;
     const uint32_t flip = (!scores_only && scale < 0.0f) ? Mma<T>::kSignMask : 0u;
     if constexpr (SPLITTABLE) {
-        // the tables hold floats: rows of the output must start on 4-byte boundaries
-        const bool aligned4 = scores_only || ((int64_t)N * (int64_t)sizeof(T)) % 4 == 0;
-        const int kc = (aligned4 && allow_split) ? key_ranges(BH * strips, (N + BN - 1) / BN) : 1;
+        const int kc = allow_split ? key_ranges(BH * strips, (N + BN - 1) / BN) : 1;
         if (kc > 1) {
             const uint64_t total = (uint64_t)BH * strips * kc;
             if (total > 0x7ffffff0u) return hipErrorInvalidValue;
@@ -695,12 +694,10 @@ hipError_t launch_ring_t(bool scores_only, const void* Q, const void* K, void* o
                            q, k, o, N, d, c, flip, strips, (uint32_t)total, 1, 0);
     if (own_tail) {
         // 32-query strips, the 128 keys of a tile over 4 waves; with so few strips their keys are split over workgroups as
-        // for problems of a few heads (SPLIT in qk_kernel: statistics through tables in P, then the weights; rows of P
-        // must start on 4-byte boundaries for the tables)
+        // for problems of a few heads (SPLIT in qk_kernel: statistics through tables in P, then the weights)
         const uint32_t tail_strips = (uint32_t)((tail_rows + 31) / 32);
         const int q_base = (int)strips * BM;
-        const bool tables_fit = scores_only || (N % 2) == 0;
-        const int kc = tables_fit ? key_ranges((int64_t)BH * tail_strips, (N + 127) / 128) : 1;
+        const int kc = key_ranges((int64_t)BH * tail_strips, (N + 127) / 128);
         const uint64_t tail_total = (uint64_t)BH * tail_strips * kc;
         const uint32_t tail_grid = (uint32_t)((tail_total + 7) / 8 * 8);
         if (kc > 1) {
@@ -744,8 +741,7 @@ hipError_t launch_qk_t(bool scores_only, const void* Q, const void* K, void* out
     const int64_t wide_units = BH * ((N + 128 * QB - 1) / (128 * QB));
     const bool big = wide_units >= 200;
     // (not below 1024 keys: two launches of a few microseconds each cost more than the idle compute units)
-    const bool tables_fit = scores_only || ((int64_t)N * (int64_t)sizeof(T)) % 4 == 0;   // floats in rows of P
-    const bool split = allow_split && !big && N >= 1024 && row_bytes > 64 && row_bytes <= 256 && tables_fit &&
+    const bool split = allow_split && !big && N >= 1024 && row_bytes > 64 && row_bytes <= 256 &&
                        key_ranges(wide_units, (N + 127) / 128) > 1;
     if constexpr (sizeof(T) == 2) {
         // Ragged lengths with enough 256-query strips for the chip: 8 waves of 32 queries that each walk whole tiles

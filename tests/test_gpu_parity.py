@@ -530,9 +530,11 @@ def test_softmax_random_shapes(src, dst, rows, cols, inplace):
                                                  ("bf16", 1, 2, 2176, 128, 0.0884), ("f32", 1, 1, 2048, 64, 0.125),
                                                  ("f32", 1, 2, 1026, 32, 0.17677669),
                                                  # rows of P off the 8-byte boundaries (tables of single floats) and, bf16
-                                                 # with an odd length, off the 4-byte ones (the weights are not split)
+                                                 # with an odd length, off the 4-byte ones (a table then starts 2 bytes
+                                                 # into its piece)
                                                  ("bf16", 1, 1, 2050, 128, 0.0884), ("f32", 1, 1, 1025, 64, 0.125),
-                                                 ("bf16", 1, 1, 2051, 64, 0.125)])
+                                                 ("bf16", 1, 1, 2051, 64, 0.125), ("bf16", 1, 2, 4097, 128, -0.0884),
+                                                 ("bf16", 1, 3, 1283, 96, 0.1)])
 def test_fused_and_scores_with_split_keys(dtype, B, H, N, d, scale):
     x = wl.fused_inputs("t", dtype, B, H, N, d, seed=8000 + N + d, scale=scale, row_factor=(0.5, 3.0) if dtype == "bf16" else None)
     P = gu.run_fused(x, guard=8192)
