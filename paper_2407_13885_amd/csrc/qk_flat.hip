@@ -189,10 +189,28 @@ void qk_flat_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict__
                         if (whole || key < N) *reinterpret_cast<uint32_t*>(rowp + key) = w01;
                         if (whole || key + 2 < N) *reinterpret_cast<uint32_t*>(rowp + key + 2) = w23;
                     } else if (whole) {
-                        rowp[key] = (uint16_t)(w01 & 0xffffu);
-                        rowp[key + 1] = (uint16_t)(w01 >> 16);
-                        rowp[key + 2] = (uint16_t)(w23 & 0xffffu);
-                        rowp[key + 3] = (uint16_t)(w23 >> 16);
+                        // Odd N: rows start on even and odd elements in turn, and 2-byte LDS writes are slow.  A row that
+                        // starts odd pairs its keys as (1, 2), (3, 4) ...: the second word of a run takes its upper half
+                        // from the run that follows in memory, which the other half-wave's lane of the same row holds
+                        // (half 0: same r4 of half 1; half 1: the next r4, or the next piece, of half 0) -- one lane
+                        // exchange per run, two aligned 4-byte writes.  The wave's first key and, where its keys end
+                        // (the next piece is another wave's, or past N), its last one have no partner here: 2 bytes each.
+                        const int par = (o + l32 * N) & 1;
+                        const bool more = r4 < 3 || (t + 1 < NT && kp + 32 < N);   // (wave-uniform) this wave holds the next run
+                        uint32_t nxt = 0u;
+                        if (r4 < 3) nxt = pack_bf16x2(X[t][4 * r4 + 4] * inv, X[t][4 * r4 + 5] * inv);
+                        else if (t + 1 < NT) nxt = pack_bf16x2(X[t + 1 < NT ? t + 1 : t][0] * inv, X[t + 1 < NT ? t + 1 : t][1] * inv);
+                        uint32_t nw = w23;
+#if defined(__HIP_DEVICE_COMPILE__)
+                        const auto sw = __builtin_amdgcn_permlane32_swap(w01, nxt, false, false);
+                        nw = half ? sw[0] : sw[1];
+#endif
+                        const uint32_t W1 = par ? __builtin_amdgcn_alignbit(w23, w01, 16) : w01;
+                        const uint32_t W2 = par ? __builtin_amdgcn_alignbit(nw, w23, 16) : w23;
+                        *reinterpret_cast<uint32_t*>(rowp + key + par) = W1;
+                        if (par && half && !more) rowp[key + 3] = (uint16_t)(w23 >> 16);
+                        else *reinterpret_cast<uint32_t*>(rowp + key + 2 + par) = W2;
+                        if (par && !half && t == 0 && r4 == 0) rowp[key] = (uint16_t)(w01 & 0xffffu);
                     } else {
                         if (key < N) rowp[key] = (uint16_t)(w01 & 0xffffu);
                         if (key + 1 < N) rowp[key + 1] = (uint16_t)(w01 >> 16);

@@ -829,10 +829,11 @@ hipError_t launch_qk(DType dt, bool scores_only, const void* Q, const void* K, v
         const int64_t units = BH * ((N + 31) / 32);
         // 128 < N <= 256 (d <= 64; the operands of the next unit are requested later in a unit, two waves per SIMD), 1024 heads,
         // fused / scores against the kernels below: N = 129, d = 64 27 / 23 against 35 / 29; 160 30 / 25 against 45 / 25; 192
-        // 38 / 33 against 49 / 27; 197 50 / 45 against 49 / 41; 224 51 / 44 against 55 / 32; d = 32: N = 144 12 / 12 against 22 / 19,
-        // 197 36 / 32 against 42 / 31, 256 31 / 28 against 42 / 27 (4096 heads: 159 / 157 against 141 / 96)
+        // 38 / 33 against 49 / 27; 197 48 / 43 against 52 / 41; 223 50 / 47 against 51 / 43; 224 51 / 44 against 55 / 32; d = 32:
+        // N = 144 12 / 12 against 22 / 19, 197 28 / 27 against 42 / 30, 256 31 / 28 against 42 / 27 (4096 heads: 159 / 157 against 141 / 96)
         const bool take = N <= 128 ? (scores_only ? ((N % 32) != 0 || units >= 2048) : !(N == 128 && units < 512))
-                                   : (scores_only ? ((N % 32) != 0 && N <= 160) : (N <= 192 || (d <= 32 && N <= 224)));
+                                   : (scores_only ? ((N % 32) != 0 && (N <= 160 || (d <= 32 && (N & 1) && N <= 224)))
+                                                  : (N <= 192 || ((d <= 32 || (N & 1)) && N <= 224)));
         if (tiny || (!force && take)) return launch_qk_tiny(scores_only, Q, K, out, BH, N, d, scale, stream);
     }
     // Short sequences whose length is not a multiple of 32 (d = 64; 197, 257, 577 ...): the kernel that stages a strip

@@ -57,6 +57,9 @@ void qk_tiny_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict__
     constexpr int NST = 2 * NKB;                  // store instructions per unit: 64 chunks each, (7 + 32 * 32 NKB) / 8 at most
     constexpr int LAST = NKB - 1;                 // the block of keys that N may cut (32 LAST < N <= 32 NKB)
     constexpr bool LATE = NKB > 4;                // where in a unit the operands of the next one are requested
+    // how an odd length is staged: 4-byte writes of pairs made up across the two half-waves, or element by element
+    // (measured: 1024 heads of N = 197, d = 32 36 -> 28 us, of N = 129, d = 64 26 -> 24; 12288 heads of N = 49 26 -> 28)
+    constexpr bool PAIRED = NKB > 4;
     __shared__ __align__(16) uint16_t blk_lds[kTinyWaves][BLK_ELEMS];
     __shared__ __align__(16) uint16_t lead_lds[kTinyWaves][8];
     __shared__ __align__(16) uint16_t dump_lds[kTinyWaves][40];   // where the keys past N of a block go (32 + a run of 4)
@@ -188,8 +191,11 @@ void qk_tiny_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict__
             uint16_t* const dumpp = dump_lds[wave] - LAST * 32;
             // GRAN bytes per staging write: 8 while N is a multiple of 4 (runs of 4 keys are whole or absent, and 8-byte
             // aligned), 4 while it is even, else 2
+            const int par = (o + l32 * N) & 1;   // (odd N) the row starts on an odd element of the staging area
             auto stage = [&](auto granc) __attribute__((always_inline)) {
                 constexpr int GRAN = decltype(granc)::value;
+                uint32_t end_val = 0u;
+                bool end_here = false;
 #pragma unroll
                 for (int kb = 0; kb < NKB; ++kb) {
 #pragma unroll
@@ -205,13 +211,52 @@ void qk_tiny_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict__
                         } else if constexpr (GRAN == 4) {
                             *reinterpret_cast<uint32_t*>(at(key)) = w01;
                             *reinterpret_cast<uint32_t*>(at(key + 2)) = w23;
-                        } else {
+                        } else if constexpr (!PAIRED) {
                             *at(key) = (uint16_t)(w01 & 0xffffu);
                             *at(key + 1) = (uint16_t)(w01 >> 16);
                             *at(key + 2) = (uint16_t)(w23 & 0xffffu);
                             *at(key + 3) = (uint16_t)(w23 >> 16);
+                        } else {
+                            // Odd N: rows start on even and odd elements in turn (`par`), and 2-byte LDS writes are slow.
+                            // A row that starts odd pairs its keys as (1, 2), (3, 4) ...: the second word of a run takes
+                            // its upper half from the run that follows in memory, which the other half-wave's lane
+                            // of the same row holds (half 0: same r4 of half 1; half 1: the next r4 of half 0) -- one lane
+                            // exchange per run, two aligned 4-byte writes.  Words with a key past N go to the dump area;
+                            // the one element per row without a partner in its own row follows below.
+                            uint32_t nxt = 0u;    // this lane's first pair of the run after this one
+                            if (r4 < 3) nxt = Wp[kb][2 * r4 + 2];
+                            else if (kb + 1 < NKB) nxt = Wp[kb + 1][0];
+                            uint32_t nw = w23;
+#if defined(__HIP_DEVICE_COMPILE__)
+                            const auto sw = __builtin_amdgcn_permlane32_swap(w01, nxt, false, false);
+                            nw = half ? sw[0] : sw[1];
+#endif
+                            const uint32_t W1 = par ? __builtin_amdgcn_alignbit(w23, w01, 16) : w01;
+                            const uint32_t W2 = par ? __builtin_amdgcn_alignbit(nw, w23, 16) : w23;
+                            const int k1 = key + par, k2 = key + 2 + par;
+                            uint16_t* const a1 = (kb < LAST || k1 + 1 < N) ? rowp + k1 : dumpp + key;
+                            uint16_t* const a2 = (kb < LAST || k2 + 1 < N) ? rowp + k2 : dumpp + key + 2;
+                            *reinterpret_cast<uint32_t*>(a1) = W1;
+                            *reinterpret_cast<uint32_t*>(a2) = W2;
+                            if (kb == LAST && !par) {     // the row's last element (N - 1 is even): the lower half of a word of its own
+                                const bool c0 = key == N - 1, c2 = key + 2 == N - 1;
+                                end_val = c0 ? w01 : (c2 ? w23 : end_val);
+                                end_here = end_here || c0 || c2;
+                            }
                         }
                     }
+                }
+                if constexpr (GRAN == 2 && PAIRED) {
+                    // the element of a row whose partner in its word belongs to the neighbouring row: the first of a
+                    // row that starts odd (key 0: half 0), the last of a row that starts even
+                    uint16_t* ae = dump_lds[wave];
+                    uint32_t ve = Wp[0][0];
+                    if (par) ae = half == 0 ? rowp : ae;
+                    else {
+                        ae = end_here ? rowp + (N - 1) : ae;
+                        ve = end_val;
+                    }
+                    *ae = (uint16_t)(ve & 0xffffu);
                 }
             };
             if ((N & 3) == 0) stage(IC<8>{});
