@@ -358,7 +358,7 @@ def cpu_baseline_softmax(x, rows=8192):
 # boundaries, head sizes that pad the K rows on chip, many short rows, few very long rows.
 # (first five: the n x n matrices of the paper's Table I)
 SHAPES_SOFTMAX = [(1024, 1024), (2048, 2048), (4096, 4096), (8192, 8192), (16384, 16384), (24576, 2048), (24576, 2047), (24576, 2040), (6000, 8200), (3000, 16385), (768, 65536), (384, 131072),
-                  (96, 524288), (16, 4194304), (100000, 512), (100000, 100), (1000000, 48)]
+                  (96, 524288), (16, 4194304), (100000, 512), (100000, 100), (1000000, 48), (602112, 49), (2000000, 8)]
 # (first five: one head of n x 128, the sizes of the paper's Table I)
 SHAPES_QK = [("bf16", 1, 1, 1024, 128), ("bf16", 1, 1, 2048, 128), ("bf16", 1, 1, 4096, 128), ("bf16", 1, 1, 8192, 128),
              ("bf16", 1, 1, 16384, 128), ("bf16", 1, 2, 4096, 128), ("bf16", 1, 4, 4096, 128), ("bf16", 1, 8, 4096, 128), ("bf16", 1, 16, 4096, 128), ("bf16", 1, 24, 4096, 128), ("bf16", 1, 32, 4096, 128), ("bf16", 1, 16, 4096, 64), ("bf16", 1, 16, 4096, 96), ("bf16", 1, 16, 4096, 256),

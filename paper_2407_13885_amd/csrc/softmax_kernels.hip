@@ -342,6 +342,90 @@ void softmax_elem_kernel(const TI* S, TO* P, int64_t rows, int cols)
     }
 }
 
+// Many short rows off the 16-byte boundaries (cols = 49, 33, 17 ...: a row per window of tokens) or of one or two chunks,
+// scores and weights of one type.  G consecutive rows -- G = 8, 4, 2 or 1 (fp32: 4, 2, 1), the fewest whose G * cols elements are whole 16-byte chunks
+// -- start on a chunk boundary again, so a WAVE takes RW rows (a multiple of G, at most 64) that are CW <= 64 whole chunks
+// of memory: lane c < CW loads chunk c (16 bytes, consecutive lanes consecutive chunks) and parks it in the wave's LDS
+// area as it lies in memory; then LPR lanes (a power of two, RW * LPR <= 64) share a row, each reads up to EPL of its
+// elements from there (Eq. 1: maximum and sum over the lanes of the row by shuffles), writes the weights back in
+// place, and lane c stores chunk c.  The rows are read and written once, 16 bytes per lane; no barrier (a wave's LDS
+// operations are served in order).  The last chunk of the matrix, if the matrix does not end on a chunk boundary,
+// is loaded and stored element by element.
+template <typename T, int EPL>
+__global__ __launch_bounds__(256)
+void softmax_packed_kernel(const T* S, T* P, int64_t rows, int cols, int RW, int CW, int LPR)
+{
+    constexpr int V = Elem<T>::VEC;
+    __shared__ __align__(16) T area_lds[4][64 * V];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    T* const area = area_lds[wave];
+    const int64_t it = (int64_t)blockIdx.x * 4 + wave;        // this wave's rows: it * RW ... (the same for its chunks)
+    const int64_t row0 = it * RW;
+    if (row0 >= rows) return;
+    const int n_rows = (int)(rows - row0 < RW ? rows - row0 : RW);
+    const int n_elems = n_rows * cols;
+    const int n_chunks = (n_elems + V - 1) / V;                // (the last one partial only at the end of the matrix)
+    const int64_t e_base = row0 * cols;                        // a multiple of V
+    const bool mine = lane < n_chunks;
+    const bool partial = mine && (lane + 1) * V > n_elems;
+
+    // ---- the chunks into LDS as they lie in memory ---------------------------------------------------------------------
+    if (mine) {
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (!partial) {
+            v = *reinterpret_cast<const u32x4*>(S + e_base + (int64_t)lane * V);
+            *reinterpret_cast<u32x4*>(area + lane * V) = v;
+        } else {
+            for (int i = 0; lane * V + i < n_elems; ++i) area[lane * V + i] = S[e_base + lane * V + i];
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    // ---- LPR lanes per row --------------------------------------------------------------------------------------------------
+    const int r = lane / LPR, part = lane - r * LPR;
+    const int epl = (cols + LPR - 1) / LPR;                     // elements per lane (<= EPL)
+    const int c0 = part * epl;
+    const bool row_here = r < n_rows;
+    T* const rowp = area + (row_here ? r : 0) * cols;
+    float x[EPL];
+    float m = -INFINITY;                                        // absent elements: below every finite score, 2^(-inf - m) = 0
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) {
+        const bool have = row_here && i < epl && c0 + i < cols;
+        x[i] = have ? Elem<T>::load1(rowp + (have ? c0 + i : 0)) : -INFINITY;
+        m = fmaxf(m, x[i]);
+    }
+    for (int off = LPR >> 1; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+    m = row_here ? m : 0.0f;                                    // (lanes without a row: keep the arithmetic finite)
+    float l = 0.0f;
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) {
+        x[i] = fast_exp2((x[i] - m) * kLog2e);
+        l += x[i];
+    }
+    for (int off = LPR >> 1; off > 0; off >>= 1) l += __shfl_xor(l, off, 64);
+    const float inv = 1.0f / l;
+#pragma unroll
+    for (int i = 0; i < EPL; ++i)
+        if (row_here && i < epl && c0 + i < cols) Elem<T>::store1(rowp + c0 + i, x[i] * inv);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    // ---- the chunks leave ----------------------------------------------------------------------------------------------------
+    if (mine) {
+        if (!partial) {
+            const u32x4 v = *reinterpret_cast<const u32x4*>(area + lane * V);
+            __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(P + e_base + (int64_t)lane * V));
+        } else {
+            for (int i = 0; lane * V + i < n_elems; ++i) P[e_base + lane * V + i] = area[lane * V + i];
+        }
+    }
+}
+
 // Rows that do not fit the registers of a workgroup, and long rows that do not start on 16-byte
 // boundaries.  The row is read twice (statistics, then weights) with 16-byte accesses: the elements of
 // a row in front of its first 16-byte boundary (of both the scores and the weights: they have the same
@@ -523,6 +607,47 @@ hipError_t launch_elem_groups(const void* S, void* P, int64_t rows, int cols, hi
     return launch_elem<TI, TO, 16 / EG, 64, EG>(S, P, rows, cols, stream);
 }
 
+// Shape of the packed kernel for rows of `cols` elements, or false if it does not take them: G rows per chunk-aligned
+// group, GW groups per wave while rows and chunks stay within 64 and a lane's share of a row within 8 elements.
+template <typename T>
+bool packed_shape(int64_t cols, int* RW, int* CW, int* LPR, int* EPL)
+{
+    constexpr int V = Elem<T>::VEC;
+    if (cols < 1) return false;
+    int G = V;
+    while (G > 1 && (cols * (G / 2)) % V == 0) G /= 2;
+    const int64_t CG = cols * G / V;
+    if (CG > 64) return false;
+    int best = 0;
+    for (int gw = 1; gw * G <= 64 && gw * CG <= 64; ++gw) {
+        int lpr = 1;
+        while (lpr * 2 * gw * G <= 64) lpr *= 2;
+        if ((cols + lpr - 1) / lpr <= 8) best = gw;
+    }
+    if (best == 0) return false;
+    *RW = best * G;
+    *CW = (int)(best * CG);
+    int lpr = 1;
+    while (lpr * 2 * *RW <= 64) lpr *= 2;
+    *LPR = lpr;
+    *EPL = (int)((cols + lpr - 1) / lpr);
+    return true;
+}
+
+template <typename T>
+hipError_t launch_packed(const void* S, void* P, int64_t rows, int cols, int RW, int CW, int LPR, int EPL, hipStream_t stream)
+{
+    const int64_t its = (rows + RW - 1) / RW;
+    if ((its + 3) / 4 > (int64_t)0x7fffffff) return hipErrorInvalidValue;
+    const dim3 grid((uint32_t)((its + 3) / 4));
+    const T* s_ = static_cast<const T*>(S);
+    T* p_ = static_cast<T*>(P);
+    if (EPL <= 2) hipLaunchKernelGGL((softmax_packed_kernel<T, 2>), grid, dim3(256), 0, stream, s_, p_, rows, cols, RW, CW, LPR);
+    else if (EPL <= 4) hipLaunchKernelGGL((softmax_packed_kernel<T, 4>), grid, dim3(256), 0, stream, s_, p_, rows, cols, RW, CW, LPR);
+    else hipLaunchKernelGGL((softmax_packed_kernel<T, 8>), grid, dim3(256), 0, stream, s_, p_, rows, cols, RW, CW, LPR);
+    return hipGetLastError();
+}
+
 template <typename T, int R, int TPR>
 hipError_t launch_rows_shifted(const void* S, void* P, int64_t rows, int64_t cols, hipStream_t stream)
 {
@@ -540,6 +665,13 @@ hipError_t launch_softmax_t(const void* S, void* P, int64_t rows, int64_t cols, 
     constexpr int E = Elem<TI>::VEC > Elem<TO>::VEC ? Elem<TI>::VEC : Elem<TO>::VEC;
     // Register-resident rows: a thread keeps up to 64 fp32 values (8 groups of 8 elements, 16 of 4).
     constexpr int MAXR = 64 / E;
+    // (many rows of one or two chunks: most lanes of the kernel below would idle -- 2 * 10^6 rows of 8 bf16 values
+    // 26 -> 12 us, 10^6 of 16 16.5 -> 13.5; from three chunks on the kernel below is as fast or faster)
+    if constexpr (sizeof(TI) == sizeof(TO)) {
+        int RW, CW, LPR, EPL;
+        if (cols % E == 0 && cols / E <= 2 && rows >= 1024 && packed_shape<TI>(cols, &RW, &CW, &LPR, &EPL))
+            return launch_packed<TI>(S, P, rows, (int)cols, RW, CW, LPR, EPL, stream);
+    }
     if (cols % E == 0 && cols / E <= 1024 * MAXR) {
         const int groups = (int)(cols / E);
         if (groups <= 4) return launch_rows<TI, TO, 1, 4>(S, P, rows, groups, stream);
@@ -556,6 +688,15 @@ hipError_t launch_softmax_t(const void* S, void* P, int64_t rows, int64_t cols, 
         if (groups <= 4096) return launch_rows<TI, TO, 4, 1024>(S, P, rows, groups, stream);
         if constexpr (MAXR >= 16) return launch_rows<TI, TO, 16, 1024>(S, P, rows, groups, stream);
         else return launch_rows<TI, TO, 8, 1024>(S, P, rows, groups, stream);
+    }
+    // many short rows off the chunk boundaries, one type: whole chunks through LDS
+    if constexpr (sizeof(TI) == sizeof(TO)) {
+        int RW, CW, LPR, EPL;
+        // (from 64 columns on only where the chunks of a wave's rows keep most of its lanes busy; measured against the
+        // kernel below, bf16: 300000 x 124 37 -> 30 us, 100000 x 252 26.5 -> 21, 300000 x 90 33 -> 30; with half the
+        // lanes loading it loses: 200000 x 132 31 -> 37)
+        if (cols < 256 && rows >= 1024 && packed_shape<TI>(cols, &RW, &CW, &LPR, &EPL) && (cols < 64 || CW >= 45))
+            return launch_packed<TI>(S, P, rows, (int)cols, RW, CW, LPR, EPL, stream);
     }
     // rows off the 16-byte boundaries, same type in and out: aligned chunks all the same, the two shared with the
     // neighbouring rows handled element by element (from 64 columns on: below, the two shared chunks are most of a row)

@@ -295,6 +295,25 @@ def test_softmax_cast_long_and_short_rows(src, dst, rows, cols):
     gu.check_weights(gu.to_f64(P), oracle.softmax(s.S, src), dst, f"softmax {src}->{dst} {rows} x {cols}")
 
 
+# Many short rows off the 16-byte boundaries, or of one or two chunks (at least 1024 rows of fewer than 64 columns): whole chunks through LDS,
+# 8, 4, 2 or 1 rows per chunk-aligned group.  Row counts that fill the last wave, leave it one row, end the matrix on
+# a chunk boundary or inside a chunk (the last chunk then goes element by element); in place; rows of the lowest value.
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("cols", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 12, 16, 17, 20, 31, 33, 36, 49, 50, 52, 62, 63, 90, 100, 124,
+                                  126, 196, 252])
+def test_softmax_many_short_rows_off_the_chunk_boundaries(dtype, cols):
+    for rows, inplace in ((1024, False), (1031, True), (4097, False)):
+        s = wl.softmax_inputs("t", dtype, rows, cols, seed=2600 + cols + rows, sigma=2.0, peak_fraction=0.01)
+        S = s.S.copy()
+        low = np.float32(-3.3895314e38) if dtype == "f32" else np.uint16(0xff7f)
+        S[5, :] = low                                # a fully masked row: uniform
+        S[rows - 1, : cols // 2] = low
+        P = gu.run_softmax(gu.to_dev(S, dtype), rows, cols, dtype, guard=0 if inplace else 4096, inplace=inplace)
+        got = gu.to_f64(P)
+        gu.check_weights(got, oracle.softmax(S, dtype), dtype, f"short rows {dtype} {rows} x {cols}")
+        assert np.abs(got[5] - 1.0 / cols).max() <= (2.0 ** -8 if dtype == "bf16" else 1e-6) / cols
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("cols", [2048, 1001, 100, 2049, 70000, 300001])
 def test_softmax_in_place(dtype, cols):
