@@ -23,14 +23,17 @@
 namespace attnw {
 namespace {
 
-constexpr int kWaves = 4;                         // waves per workgroup (independent of each other)
+// waves per workgroup (independent of each other): four, or two where four waves' areas for V would take the LDS of a
+// compute unit for one workgroup (d = 64 with more than 64 keys: 16 KiB of V per wave)
+template <int NKB, int DB> constexpr int waves_of() { return NKB * DB > 4 ? 2 : 4; }
 
 // NKB: 32-key blocks of a head (32 (NKB - 1) < N <= 32 NKB); DB: 32-column blocks of the head size (d = 32 DB)
 template <int NKB, int DB>
-__global__ __launch_bounds__(64 * kWaves, 2)
+__global__ __launch_bounds__((NKB * DB > 4 ? 128 : 256), 2)
 void attention_tiny_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
                            uint16_t* __restrict__ O, int N, float c, uint32_t sign_flip, uint32_t total_units)
 {
+    constexpr int kWaves = waves_of<NKB, DB>();
     constexpr int G = 2 * DB;                     // 16-element steps of the score contraction
     constexpr int D = 32 * DB;
     constexpr int ROW_B = 2 * D;                  // bytes of a row of Q, K, V, O
@@ -239,6 +242,7 @@ void attention_tiny_kernel(const uint16_t* __restrict__ Q, const uint16_t* __res
 template <int NKB, int DB>
 hipError_t launch_t(const void* Q, const void* K, const void* V, void* O, int64_t BH, int N, float scale, hipStream_t stream)
 {
+    constexpr int kWaves = waves_of<NKB, DB>();
     const uint32_t total = (uint32_t)(BH * ((N + 31) / 32));
     static const int per_cu = [] {
         int n = 0;
@@ -257,17 +261,16 @@ hipError_t launch_t(const void* Q, const void* K, const void* V, void* O, int64_
 
 }  // namespace
 
-// (the V operands of a unit are 16 NKB DB gathers of two bytes per lane: N <= 64 with d = 64, N <= 128 with d = 32)
 bool attention_tiny_supported(int64_t BH, int64_t N, int64_t d)
 {
     if (N < 1 || N > 128 || (d != 32 && d != 64)) return false;
-    if (d == 64 && N > 64) return false;
     return BH * ((N + 31) / 32) <= (int64_t)0x7ffffff0;
 }
 
 // Measured against the tiled kernel, us (heads x N, d): 12288 x 49, 32 122 -> 30; 12288 x 64, 32 119 -> 38; 12288 x 100, 32
 // 133 -> 81; 12288 x 128, 32 145 -> 137; 12288 x 49, 64 242 -> 57; 12288 x 64, 64 252 -> 90; 1024 x 32, 64 20 -> 4.3; 16 to 256
-// heads: within 0.5 us of each other either way.
+// heads: within 0.5 us of each other either way.  d = 64 beyond 64 keys (two waves per workgroup), 1024 heads: N = 65
+// 22 -> 12, 96 26 -> 14, 100 26.5 -> 19, 128 29.5 -> 24.5; 12288 heads of N = 128: 307 -> 268.
 bool prefers_attention_tiny(int64_t BH, int64_t N, int64_t d)
 {
     (void)BH; (void)N; (void)d;
@@ -285,7 +288,9 @@ hipError_t launch_attention_tiny(const void* Q, const void* K, const void* V, vo
         return launch_t<4, 1>(Q, K, V, O, BH, n, scale, stream);
     }
     if (n <= 32) return launch_t<1, 2>(Q, K, V, O, BH, n, scale, stream);
-    return launch_t<2, 2>(Q, K, V, O, BH, n, scale, stream);
+    if (n <= 64) return launch_t<2, 2>(Q, K, V, O, BH, n, scale, stream);
+    if (n <= 96) return launch_t<3, 2>(Q, K, V, O, BH, n, scale, stream);
+    return launch_t<4, 2>(Q, K, V, O, BH, n, scale, stream);
 }
 
 }  // namespace attnw
