@@ -173,8 +173,8 @@ int attnw_scale(const void *X, void *Y, int64_t count, float scale,
  * store.  (d up to 128 runs tiled through on-chip memory -- d = 32, 64, 128 with N
  * a multiple of 256 on the fast path, other head sizes padded on chip, other
  * lengths with the rows past the end clamped and masked; few heads are spread over
- * the chip by key ranges; sequences of up to 128 tokens with d = 32 or 64 run a wave
- * per head and 32 queries without on-chip tiles.  Larger d reads its
+ * the chip by key ranges; sequences of up to 128 tokens with d = 64, or 160 with
+ * d = 32, run a wave per head and 32 queries without on-chip tiles.  Larger d reads its
  * operands straight from device memory.  ATTNW_ATTENTION_KERNEL=tiny / =tiled in the
  * environment puts every shape that the wave-per-head kernel takes on it / none.)
  * ATTNW_F32: d a multiple of 4 up to 256, any N >= 1.  Both contractions on the

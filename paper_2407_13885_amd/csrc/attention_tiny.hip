@@ -263,7 +263,7 @@ hipError_t launch_t(const void* Q, const void* K, const void* V, void* O, int64_
 
 bool attention_tiny_supported(int64_t BH, int64_t N, int64_t d)
 {
-    if (N < 1 || N > 128 || (d != 32 && d != 64)) return false;
+    if (N < 1 || N > (d == 32 ? 224 : 128) || (d != 32 && d != 64)) return false;   // (beyond: scores and operands exceed the registers)
     return BH * ((N + 31) / 32) <= (int64_t)0x7ffffff0;
 }
 
@@ -271,10 +271,12 @@ bool attention_tiny_supported(int64_t BH, int64_t N, int64_t d)
 // 133 -> 81; 12288 x 128, 32 145 -> 137; 12288 x 49, 64 242 -> 57; 12288 x 64, 64 252 -> 90; 1024 x 32, 64 20 -> 4.3; 16 to 256
 // heads: within 0.5 us of each other either way.  d = 64 beyond 64 keys (two waves per workgroup), 1024 heads: N = 65
 // 22 -> 12, 96 26 -> 14, 100 26.5 -> 19, 128 29.5 -> 24.5; 12288 heads of N = 128: 307 -> 268.
+// d = 32 beyond 128 keys (two waves per workgroup), 3072 heads: N = 129 52 -> 34, 144 60 -> 40, 160 55 -> 44; 197 57 -> 79 and
+// 224 58 -> 91: not taken from 161 keys on.
 bool prefers_attention_tiny(int64_t BH, int64_t N, int64_t d)
 {
-    (void)BH; (void)N; (void)d;
-    return true;
+    (void)BH; (void)d;
+    return N <= 160;
 }
 
 hipError_t launch_attention_tiny(const void* Q, const void* K, const void* V, void* O, int64_t BH, int64_t N, int64_t d,
@@ -285,7 +287,10 @@ hipError_t launch_attention_tiny(const void* Q, const void* K, const void* V, vo
         if (n <= 32) return launch_t<1, 1>(Q, K, V, O, BH, n, scale, stream);
         if (n <= 64) return launch_t<2, 1>(Q, K, V, O, BH, n, scale, stream);
         if (n <= 96) return launch_t<3, 1>(Q, K, V, O, BH, n, scale, stream);
-        return launch_t<4, 1>(Q, K, V, O, BH, n, scale, stream);
+        if (n <= 128) return launch_t<4, 1>(Q, K, V, O, BH, n, scale, stream);
+        if (n <= 160) return launch_t<5, 1>(Q, K, V, O, BH, n, scale, stream);
+        if (n <= 192) return launch_t<6, 1>(Q, K, V, O, BH, n, scale, stream);
+        return launch_t<7, 1>(Q, K, V, O, BH, n, scale, stream);
     }
     if (n <= 32) return launch_t<1, 2>(Q, K, V, O, BH, n, scale, stream);
     if (n <= 64) return launch_t<2, 2>(Q, K, V, O, BH, n, scale, stream);

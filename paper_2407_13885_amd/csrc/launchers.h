@@ -67,7 +67,7 @@ bool attention_general_supported(DType dt, int64_t BH, int64_t N, int64_t d);
 hipError_t launch_attention_general(DType dt, const void* Q, const void* K, const void* V, void* O, int64_t BH, int64_t N,
                                     int64_t d, float scale, hipStream_t stream);
 
-// The same for many short sequences (bf16, d = 32 or 64, N <= 128): a wave per (head, 32 queries), operands
+// The same for many short sequences (bf16, d = 64 with N <= 128, d = 32 with N <= 224): a wave per (head, 32 queries), operands
 // straight from global memory, the exponentials as they stand the operand of the second contraction.
 bool attention_tiny_supported(int64_t BH, int64_t N, int64_t d);
 bool prefers_attention_tiny(int64_t BH, int64_t N, int64_t d);

@@ -1,4 +1,4 @@
-"""GPU parity of attnw_attention on many short sequences (bf16, d = 32 or 64, N <= 128: the kernel in
+"""GPU parity of attnw_attention on many short sequences (bf16, d = 64 with N <= 128, d = 32 with N <= 224: the kernel in
 which a wave works alone on a (head, 32 queries) pair) against the fp64 oracle, at the bar of test_gpu_attention.py:
 the weights are rounded to bf16 before they multiply V and the output once more, so with A_it = sum_j P_ij |V_jt|
 the bound is 2^-8 (A_it + |O_it|) (two roundings of 2^-9 each) plus the fp32 accumulation."""
@@ -57,14 +57,15 @@ def _check(B, H, N, d, scale=None, seed=0, row_factor=(0.5, 2.0)):
 # one to four blocks of keys and queries, last blocks of 1 and of 31 keys, lengths below a block
 @pytest.mark.parametrize("N,d", [(1, 32), (2, 64), (7, 32), (31, 64), (32, 32), (33, 64), (49, 32), (49, 64), (63, 32), (64, 64),
                                  (64, 32), (65, 32), (96, 32), (97, 32), (100, 32), (127, 32), (128, 32),
-                                 (65, 64), (96, 64), (97, 64), (100, 64), (127, 64), (128, 64)])
+                                 (65, 64), (96, 64), (97, 64), (100, 64), (127, 64), (128, 64),
+                                 (129, 32), (144, 32), (160, 32), (161, 32), (192, 32), (197, 32), (223, 32), (224, 32)])
 def test_any_length(N, d, monkeypatch):
     monkeypatch.setenv("ATTNW_ATTENTION_KERNEL", "tiny")
     _check(1, 5, N, d)
 
 
 @pytest.mark.parametrize("B,H,N,d", [(100, 7, 49, 32), (4096, 3, 49, 32), (300, 4, 64, 64), (500, 3, 100, 32), (90, 12, 33, 64),
-                                     (2000, 1, 20, 32), (64, 12, 128, 64), (100, 8, 100, 64)])
+                                     (2000, 1, 20, 32), (64, 12, 128, 64), (100, 8, 100, 64), (256, 12, 144, 32), (64, 16, 160, 32)])
 def test_many_heads_by_default(B, H, N, d):
     """The shapes that take this kernel without being asked; more (head, 32 queries) units than resident waves: unit
     ranges that cross head boundaries."""
