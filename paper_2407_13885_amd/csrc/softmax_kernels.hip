@@ -680,14 +680,31 @@ hipError_t launch_softmax_t(const void* S, void* P, int64_t rows, int64_t cols, 
         if (groups <= 32) return launch_rows<TI, TO, 1, 32>(S, P, rows, groups, stream);
         if (groups <= 64) return launch_rows<TI, TO, 1, 64>(S, P, rows, groups, stream);
         if (groups <= 128) return launch_rows<TI, TO, 2, 64>(S, P, rows, groups, stream);
+        // (lanes times groups per lane just above the row where it was measured to pay -- a shape with half of its
+        // slots empty has half of the bytes in flight per compute unit; bf16: 100000 x 1032 83 -> 69 us,
+        // 24576 x 2056 39 -> 36.5, 6000 x 8200 41 -> 34, 6000 x 10240 44 -> 40; fp32: 50000 x 516 39 -> 37;
+        // three groups on 128 or 256 lanes, six on 256 and five of 4 elements: no faster than the next shape up)
+        if (groups <= 192) return launch_rows<TI, TO, 3, 64>(S, P, rows, groups, stream);
         // (two waves per row here: 2 % faster than one wave with four groups per lane on 24576 x 2048 bf16)
         if (groups <= 256) return launch_rows<TI, TO, 2, 128>(S, P, rows, groups, stream);
+        if constexpr (E == 8) {
+            if (groups <= 320) return launch_rows<TI, TO, 5, 64>(S, P, rows, groups, stream);
+        }
         if (groups <= 512) return launch_rows<TI, TO, 2, 256>(S, P, rows, groups, stream);
         if (groups <= 1024) return launch_rows<TI, TO, 4, 256>(S, P, rows, groups, stream);
+        if constexpr (E == 8) {
+            if (groups <= 1280) return launch_rows<TI, TO, 5, 256>(S, P, rows, groups, stream);
+        }
         if (groups <= 2048) return launch_rows<TI, TO, 2, 1024>(S, P, rows, groups, stream);
         if (groups <= 4096) return launch_rows<TI, TO, 4, 1024>(S, P, rows, groups, stream);
-        if constexpr (MAXR >= 16) return launch_rows<TI, TO, 16, 1024>(S, P, rows, groups, stream);
-        else return launch_rows<TI, TO, 8, 1024>(S, P, rows, groups, stream);
+        if (groups <= 6144) return launch_rows<TI, TO, 6, 1024>(S, P, rows, groups, stream);
+        if constexpr (MAXR >= 16) {
+            // (eight groups of 4 elements on 1024 lanes: the compiler spills registers for that one shape)
+            if (groups <= 12288) return launch_rows<TI, TO, 12, 1024>(S, P, rows, groups, stream);
+            return launch_rows<TI, TO, 16, 1024>(S, P, rows, groups, stream);
+        } else {
+            return launch_rows<TI, TO, 8, 1024>(S, P, rows, groups, stream);
+        }
     }
     // many short rows off the chunk boundaries, one type: whole chunks through LDS
     if constexpr (sizeof(TI) == sizeof(TO)) {

@@ -405,6 +405,34 @@ def test_gemm_scores_round_kernel_negative_scale_matches_general_kernel(monkeypa
     assert torch.equal(S.view(torch.int16), S2.view(torch.int16))
 
 
+# Rows that start on 16-byte boundaries are kept in registers as groups of 8 (a 16-bit type on either side) or 4
+# elements, lanes per row and groups per lane chosen by the number of groups: the counts at which the choice
+# changes, and one past each, for every pair of types.
+@pytest.mark.parametrize("src,dst", [("bf16", "bf16"), ("f32", "f32"), ("f32", "bf16"), ("bf16", "f32")])
+@pytest.mark.parametrize("groups", [64, 65, 128, 129, 192, 193, 256, 257, 320, 321, 512, 513, 1024, 1025, 1280, 1281,
+                                    2048, 2049, 4096, 4097, 6144, 6145, 8192])
+def test_softmax_groups_per_row_at_the_steps_of_the_launch_shapes(src, dst, groups):
+    import paper_2407_13885_amd as attnw
+    e = 4 if (src, dst) == ("f32", "f32") else 8
+    cols = groups * e
+    rows = 5 if groups <= 64 * 5 else 3
+    s = wl.softmax_inputs("t", src, rows, cols, seed=2100 + groups, sigma=2.0, peak_fraction=0.005)
+    S = gu.to_dev(s.S, src)
+    P, canary = gu.empty_like_out((rows, cols), dst, guard=4096)
+    attnw.attnw_softmax_cast(S, P, rows, cols, gu.DT[src], gu.DT[dst])
+    torch.cuda.synchronize()
+    assert gu.guards_intact(canary), "softmax wrote outside P"
+    gu.check_weights(gu.to_f64(P), oracle.softmax(s.S, src), dst, f"softmax {src}->{dst} {rows} x {cols}")
+
+
+@pytest.mark.parametrize("groups", [8193, 12288, 12289, 16384])
+def test_softmax_fp32_rows_of_up_to_sixteen_groups_per_lane(groups):
+    rows, cols = 3, groups * 4
+    s = wl.softmax_inputs("t", "f32", rows, cols, seed=2200 + groups, sigma=2.0, peak_fraction=0.005)
+    P = gu.run_softmax(gu.to_dev(s.S, "f32"), rows, cols, "f32", guard=4096)
+    gu.check_weights(gu.to_f64(P), oracle.softmax(s.S, "f32"), "f32", f"softmax f32 {rows} x {cols}")
+
+
 # ---- softmax with separate storage types for scores and weights ------------------------------------
 
 @pytest.mark.parametrize("src,dst", [("f32", "bf16"), ("bf16", "f32")])
