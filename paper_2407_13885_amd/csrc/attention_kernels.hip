@@ -133,15 +133,20 @@ void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
 
     // ---- per-lane constants ----------------------------------------------------------------------------
     // K tile transfer j of this lane: key within the tile (recomputed where a clamp needs it), byte offset in the tile
-    auto k_key = [&](int j) __attribute__((always_inline)) { return ((wave + NW * j) * 64 + lane) / CPR; };
-    int k_off[K_LOADS];
-#pragma unroll
-    for (int j = 0; j < K_LOADS; ++j) {
-        const int s = (wave + NW * j) * 64 + lane;
-        int ch = (s % CPR) ^ ((k_key(j) / C::RPL) & C::SWZ_MASK);
+    // (s = (wave + NW j) 64 + lane is transfer j's chunk of the tile: its chunk within the row, and the bits of its key
+    // that the swizzle takes, do not depend on j -- one offset per lane and a constant step per transfer, instead of
+    // a 64-bit offset register pair per transfer)
+    constexpr int KSTEP = NW * 64 / CPR;          // keys between transfers j and j + 1 of a lane
+    static_assert((NW * 64) % CPR == 0 && KSTEP % C::RPL == 0 && (KSTEP / C::RPL) % (C::SWZ_MASK + 1) == 0, "K transfer shape");
+    auto k_key = [&](int j) __attribute__((always_inline)) { return (wave * 64 + lane) / CPR + KSTEP * j; };
+    int k_off0;
+    {
+        const int s = wave * 64 + lane;
+        int ch = (s % CPR) ^ ((k_key(0) / C::RPL) & C::SWZ_MASK);
         if (PAD && ch * 16 >= rb) ch = 0;         // a padding chunk: any finite data of the row
-        k_off[j] = k_key(j) * rb + ch * 16;
+        k_off0 = k_key(0) * rb + ch * 16;
     }
+    auto k_off = [&](int j) __attribute__((always_inline)) { return k_off0 + j * KSTEP * rb; };
     const uint32_t k_lds_base = lds_offset_of(k_lds);
     int kfrag_off[G];
     {
@@ -151,16 +156,19 @@ void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
     }
     // V tile: wave-wide load j covers 64 consecutive keys x one 16-byte chunk (8 output columns); the
     // 8 values go to 8 Vt rows at the key's permuted position (64 lanes -> 128 contiguous bytes per row)
-    auto v_key = [&](int j) __attribute__((always_inline)) { return ((wave + NW * j) & 1) * 64 + lane; };
-    int v_off[V_LOADS], v_ldsoff[V_LOADS];
-#pragma unroll
-    for (int j = 0; j < V_LOADS; ++j) {
-        const int key = v_key(j);
-        const int ch = (wave + NW * j) >> 1;
-        const int pos = (key & ~12) | ((key & 4) << 1) | ((key & 8) >> 1);   // bits 2 and 3 swapped
-        v_off[j] = key * rb + ch * 16;
-        v_ldsoff[j] = ch * 8 * VT_PITCH + pos * 2;
+    // (NW is even: the half of the tile is the same for every j, the chunk advances by NW / 2)
+    static_assert(NW % 2 == 0, "V load shape");
+    const int v_key0 = (wave & 1) * 64 + lane;
+    auto v_key = [&](int) __attribute__((always_inline)) { return v_key0; };
+    int v_off0, v_ldsoff0;
+    {
+        const int ch = wave >> 1;
+        const int pos = (v_key0 & ~12) | ((v_key0 & 4) << 1) | ((v_key0 & 8) >> 1);   // bits 2 and 3 swapped
+        v_off0 = v_key0 * rb + ch * 16;
+        v_ldsoff0 = ch * 8 * VT_PITCH + pos * 2;
     }
+    auto v_off = [&](int j) __attribute__((always_inline)) { return v_off0 + j * (NW / 2) * 16; };
+    auto v_ldsoff = [&](int j) __attribute__((always_inline)) { return v_ldsoff0 + j * (NW / 2) * 8 * VT_PITCH; };
     // Vt fragment of (block dvb, sub-tile u, group m): row dvb*32 + l32, keys u*32 + 16m + 8*half ..
     const int vfrag_off = l32 * VT_PITCH + half * 16;
 
@@ -172,7 +180,7 @@ void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
         const bool clamp = TAIL && tile == n_tiles - 1;
 #pragma unroll
         for (int i = 0; i < K_LOADS; ++i) {
-            const char* src = tile_base + k_off[i];
+            const char* src = tile_base + k_off(i);
             if (clamp) src -= (int64_t)(tile * BN + k_key(i) - row_in(tile * BN + k_key(i))) * rb;
             dma16_untracked(src, k_lds_base + buf * K_TILE_BYTES + (wave + NW * i) * 1024);
         }
@@ -183,7 +191,7 @@ void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
         const bool clamp = TAIL && tile == n_tiles - 1;
 #pragma unroll
         for (int j = 0; j < V_LOADS; ++j) {
-            const char* src = tile_base + v_off[j];
+            const char* src = tile_base + v_off(j);
             if (clamp) src -= (int64_t)(tile * BN + v_key(j) - row_in(tile * BN + v_key(j))) * rb;
             if (PAD && (int)(((wave + NW * j) >> 1) * 16) >= rb) vreg[j] = u32x4{0u, 0u, 0u, 0u};   // columns past the end
             else vreg[j] = *reinterpret_cast<const u32x4*>(src);
@@ -196,7 +204,7 @@ void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const uint32_t w = vreg[j][e / 2];
-                *reinterpret_cast<uint16_t*>(base + v_ldsoff[j] + e * VT_PITCH) = (uint16_t)((e & 1) ? (w >> 16) : (w & 0xffffu));
+                *reinterpret_cast<uint16_t*>(base + v_ldsoff(j) + e * VT_PITCH) = (uint16_t)((e & 1) ? (w >> 16) : (w & 0xffffu));
             }
     };
 
