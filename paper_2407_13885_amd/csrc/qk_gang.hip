@@ -23,10 +23,15 @@
 //
 // The only memory a call may write is P, so the exchange tables live in P itself: the pair table of
 // strip s of a workgroup is parked in the part of P that the SAME workgroup fills with the weights
-// of its next strip, s + 1.  Nobody else ever writes there, and the workgroup overwrites it only
-// after it has seen every peer's table of strip s + 1 -- which a peer publishes only after it has
-// read the tables of strip s.  The table of the last strip of a list has no next strip: it is parked
-// in the strip's own block and the peers acknowledge having read it before the block is written.
+// of the strip after its next one, s + 2.  Nobody else ever writes there, and the workgroup writes
+// those weights, two iterations after it took their exponentials, only after it has folded every
+// peer's table of strip s + 2 -- which a peer publishes only after it has folded the tables of strip
+// s (fold, barrier, publish, in this order within an iteration).  One strip less of distance is not
+// enough: a peer starts READING the tables of strip s only after it has published its table of strip
+// s + 1, so a workgroup that had waited for that table could overwrite what the peer was about to
+// read (seen as whole strips with wrong sums in a gang whose members ran at different speeds).  The
+// tables of the last two strips of a list have no such strip: they are parked in the last strip's
+// own block (rows 1 and 3) and the peers acknowledge having read them before the block is written.
 // A small kernel launched in front zeroes the table slots (a slot is valid once its sum is non-zero:
 // a sum of exponentials against the own maximum is at least 1).
 //
@@ -163,8 +168,9 @@ __device__ __forceinline__ int64_t slot_offset(uint32_t bh, uint32_t strip, int 
     return (((int64_t)bh * N + (int64_t)strip * 32 + row) * (int64_t)N + (int64_t)j * kr) * 2;
 }
 
-// Zeroes the table slots the main kernel waits on: row 0 of every block but the first of a segment (the
-// previous strip's pairs), rows 1 and 2 of the last block of a segment (its own pairs, the acknowledgements).
+// Zeroes the table slots the main kernel waits on: row 0 of every block but the first two of a segment (the
+// pairs of the strip two before), rows 1, 2 and 3 of the last block of a segment (its own pairs, the
+// acknowledgements, the pairs of the strip before).
 template <int KR>
 __global__ __launch_bounds__(256)
 void qk_gang_init_kernel(uint16_t* __restrict__ out, int N, uint32_t gsize, uint32_t strips_per_head, uint32_t total_strips)
@@ -176,12 +182,13 @@ void qk_gang_init_kernel(uint16_t* __restrict__ out, int N, uint32_t gsize, uint
     // one 32-lane group per strip, 8 strips per trip
     for (uint32_t s = w.s_a + (tid >> 5); s < w.s_b; s += 8) {
         const uint32_t bh = s / strips_per_head, strip = s - bh * strips_per_head;
-        const bool first = s == w.s_a || strip == 0;
+        const uint32_t seg_first = max(w.s_a, bh * strips_per_head);   // first strip of the segment, global index
         const bool last = s + 1 == w.s_b || strip + 1 == strips_per_head;
-        if (!first) *reinterpret_cast<uint64_t*>(base + slot_offset(bh, strip, 0, w.r, N, KR) + q * 8) = 0ull;
+        if (s - seg_first >= 2) *reinterpret_cast<uint64_t*>(base + slot_offset(bh, strip, 0, w.r, N, KR) + q * 8) = 0ull;
         if (last) {
-            *reinterpret_cast<uint64_t*>(base + slot_offset(bh, strip, 1, w.r, N, KR) + q * 8) = 0ull;
-            *reinterpret_cast<uint64_t*>(base + slot_offset(bh, strip, 2, w.r, N, KR) + q * 8) = 0ull;
+#pragma unroll
+            for (int row = 1; row <= 3; ++row)
+                *reinterpret_cast<uint64_t*>(base + slot_offset(bh, strip, row, w.r, N, KR) + q * 8) = 0ull;
         }
     }
 }
@@ -291,9 +298,9 @@ void qk_gang_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict__
             return Qh + (uint32_t)((strip * 32 + l32) * DB + half * 16);
         };
         // byte offset in the head's part of P of the table of segment-relative strip i as published by key range j:
-        // row 0 of the block of strip i + 1, or, for the last strip of the segment, row 1 of its own block
+        // row 0 of the block of strip i + 2, or, for the last two strips of the segment, rows 3 and 1 of the last block
         auto table_off = [&](uint32_t i, uint32_t j) __attribute__((always_inline)) -> uint32_t {
-            return i + 1 < n ? blk_off(s0 + i + 1, 0, j) : blk_off(s0 + i, 1, j);
+            return i + 2 < n ? blk_off(s0 + i + 2, 0, j) : blk_off(s0 + n - 1, i + 1 == n ? 1 : 3, j);
         };
         // start the transfer of the tables of strip i of this wave's four peers into LDS (lane: peer lane / 16,
         // 16 bytes lane % 16 of its 256-byte table; a peer that does not exist, or this workgroup itself: the own table)
