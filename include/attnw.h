@@ -25,8 +25,9 @@
  *     registers of a workgroup, and for attention weights of so few heads that
  *     the keys of a strip are split over workgroups -- the first launch then
  *     uses parts of P as scratch --, or whose last few queries of a ragged
- *     length get one or two launches of their own) and nothing else on the
- *     stream, so it can be
+ *     length get one or two launches of their own; two for an attention output
+ *     whose last few queries of a ragged length get a launch of their own) and
+ *     nothing else on the stream, so it can be
  *     recorded by stream capture and replayed as part of a graph.
  *   - Return value: ATTNW_OK (0) or a negative attnw_status.  Nothing throws or
  *     aborts.  Arguments are validated before any HIP call, in this order:

@@ -84,7 +84,7 @@ struct AttnCfg {
 template <int DB, int QB, bool TAIL, bool PAD = false, int WK = 1>
 __global__ __launch_bounds__(512)
 void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
-                      uint16_t* __restrict__ O, int N, int rb_arg, float c, uint32_t sign_flip, uint32_t strips, uint32_t total)
+                      uint16_t* __restrict__ O, int N, int rb_arg, float c, uint32_t sign_flip, uint32_t strips, uint32_t total, int q_base)
 {
     const int rb = PAD ? rb_arg : DB;             // bytes of a row in memory
     using C = AttnCfg<DB, QB, WK>;
@@ -115,7 +115,7 @@ void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
     const char* Vh = reinterpret_cast<const char*>(V) + (int64_t)bh * N * rb;
     char* Oh = reinterpret_cast<char*>(O) + (int64_t)bh * N * rb;
     const int wq = wave / WK, wk = wave % WK;     // query block of the wave, its key range within every tile
-    const int q0 = strip * BM + wq * QW;
+    const int q0 = q_base + strip * BM + wq * QW;   // (q_base: the launch covers the strips from that query on)
 
     auto row_in = [&](int r) __attribute__((always_inline)) { return TAIL ? min(r, N - 1) : r; };
 
@@ -393,20 +393,43 @@ void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict
     }
 }
 
+// Queries [q_base, q_end) of every head (q_end < 0: up to N); q_base is a multiple of the strip height.
 template <int DB, int QB, bool TAIL, bool PAD = false, int WK = 1>
 hipError_t launch_attention_t(const void* Q, const void* K, const void* V, void* O, int64_t BH, int N, float scale,
-                              hipStream_t stream, int d = DB / 2)
+                              hipStream_t stream, int d = DB / 2, int q_base = 0, int q_end = -1)
 {
     using C = AttnCfg<DB, QB, WK>;
-    const uint32_t strips = (uint32_t)((N + C::BM - 1) / C::BM);
+    const int rows = (q_end < 0 ? N : q_end) - q_base;
+    const uint32_t strips = (uint32_t)((rows + C::BM - 1) / C::BM);
     const uint64_t total = (uint64_t)BH * strips;
     const uint32_t grid = (uint32_t)((total + 7) / 8 * 8);
     const float c = fabsf(scale) * kLog2e;
     const uint32_t flip = scale < 0.0f ? Mma<uint16_t>::kSignMask : 0u;
     hipLaunchKernelGGL((attention_kernel<DB, QB, TAIL, PAD, WK>), dim3(grid), dim3(512), 0, stream, static_cast<const uint16_t*>(Q),
                        static_cast<const uint16_t*>(K), static_cast<const uint16_t*>(V), static_cast<uint16_t*>(O), N, 2 * d,
-                       c, flip, strips, (uint32_t)total);
+                       c, flip, strips, (uint32_t)total, q_base);
     return hipGetLastError();
+}
+
+// A ragged length whose last strip (256 queries, 512 with two query blocks per wave) holds at most 64 queries, and whose partial strips start another round
+// of workgroups on the chip: such a workgroup spends what ONE of its waves spends on a full strip -- the whole sweep
+// over the keys -- on a few rows.  The partial strips are left out of the launch and follow as a second one with
+// 64-query strips whose keys are spread over four waves (a quarter of the sweep per wave).  Measured: 64 heads of
+// N = 2049, d = 64: 146 -> 103 us; 128 heads of N = 1025: 74 -> 66 us; 16 heads of N = 4097, d = 128: 209 -> 202 us
+// (33 tiles at the load latency of a tile each: the second launch alone takes 60 us there).
+template <int DB, int QB = 1>
+hipError_t launch_attention_own_tail(const void* Q, const void* K, const void* V, void* O, int64_t BH, int N, float scale,
+                                     hipStream_t stream, bool* taken)
+{
+    constexpr int BM = 256 * QB;
+    const int64_t full = N / BM, tail_rows = N - full * BM;
+    const int64_t slots = (int64_t)compute_units() * (DB == 64 && QB == 1 ? 2 : 1);   // (co-resident workgroups: registers)
+    *taken = full >= 1 && tail_rows >= 1 && tail_rows <= 64 &&
+             (BH * full + slots - 1) / slots < (BH * (full + 1) + slots - 1) / slots;
+    if (!*taken) return hipSuccess;
+    const hipError_t e = launch_attention_t<DB, QB, true>(Q, K, V, O, BH, N, scale, stream, DB / 2, 0, (int)(full * BM));
+    if (e != hipSuccess) return e;
+    return launch_attention_t<DB, 1, true, false, 4>(Q, K, V, O, BH, N, scale, stream, DB / 2, (int)(full * BM));
 }
 
 }  // namespace
@@ -447,18 +470,31 @@ hipError_t launch_attention(const void* Q, const void* K, const void* V, void* O
     }
     if (d == 32) {          // short rows: two query blocks per wave whenever that leaves enough workgroups
         const bool wide = N >= 2048 && BH * ((N + 511) / 512) >= 200;
-        if ((N % 256) != 0)
-            return wide ? launch_attention_t<64, 2, true>(Q, K, V, O, BH, (int)N, scale, stream)
-                        : launch_attention_t<64, 1, true>(Q, K, V, O, BH, (int)N, scale, stream);
+        if ((N % 256) != 0) {
+            bool taken;
+            if (wide) {
+                const hipError_t e = launch_attention_own_tail<64, 2>(Q, K, V, O, BH, (int)N, scale, stream, &taken);
+                return taken ? e : launch_attention_t<64, 2, true>(Q, K, V, O, BH, (int)N, scale, stream);
+            }
+            const hipError_t e = launch_attention_own_tail<64>(Q, K, V, O, BH, (int)N, scale, stream, &taken);
+            return taken ? e : launch_attention_t<64, 1, true>(Q, K, V, O, BH, (int)N, scale, stream);
+        }
         return (wide && (N % 512) == 0) ? launch_attention_t<64, 2, false>(Q, K, V, O, BH, (int)N, scale, stream)
                                         : launch_attention_t<64, 1, false>(Q, K, V, O, BH, (int)N, scale, stream);
     }
     if ((N % 256) != 0) {   // any length: rows past the end are clamped and masked
-        if (d == 128) return launch_attention_t<256, 1, true>(Q, K, V, O, BH, (int)N, scale, stream);
+        bool taken;
+        if (d == 128) {
+            const hipError_t e = launch_attention_own_tail<256>(Q, K, V, O, BH, (int)N, scale, stream, &taken);
+            return taken ? e : launch_attention_t<256, 1, true>(Q, K, V, O, BH, (int)N, scale, stream);
+        }
         // (512-query strips only where the rows a last strip leaves unused are a small share)
-        if (N >= 2048 && BH * ((N + 511) / 512) >= 200)
-            return launch_attention_t<128, 2, true>(Q, K, V, O, BH, (int)N, scale, stream);
-        return launch_attention_t<128, 1, true>(Q, K, V, O, BH, (int)N, scale, stream);
+        if (N >= 2048 && BH * ((N + 511) / 512) >= 200) {
+            const hipError_t e = launch_attention_own_tail<128, 2>(Q, K, V, O, BH, (int)N, scale, stream, &taken);
+            return taken ? e : launch_attention_t<128, 2, true>(Q, K, V, O, BH, (int)N, scale, stream);
+        }
+        const hipError_t e = launch_attention_own_tail<128>(Q, K, V, O, BH, (int)N, scale, stream, &taken);
+        return taken ? e : launch_attention_t<128, 1, true>(Q, K, V, O, BH, (int)N, scale, stream);
     }
     if (d == 128) return launch_attention_t<256, 1, false>(Q, K, V, O, BH, (int)N, scale, stream);
     // two query blocks per wave (512-query strips) when that still gives every compute unit a workgroup

@@ -130,6 +130,21 @@ def test_attention_any_length_long(B, H, N, d):
         _check_rows(O[0, hh], x, V, 0, hh, [(0, 70), (500, 530), (2040, N)], f"attention {B}x{H}x{N}x{d} head {hh}")
 
 
+# A last strip of at most 64 queries that would start another round of workgroups is left out of the launch and
+# follows as a second one with its keys spread over four waves: 256-query strips at d = 32 / 64 / 128, 512-query strips
+# (two query blocks per wave); a tail of 1, 33 and 64 rows; next to it a length whose tail is too long for the rule.
+@pytest.mark.parametrize("B,H,N,d", [(1, 64, 1025, 64), (1, 128, 545, 32), (1, 32, 2081, 128), (1, 64, 2049, 64),
+                                     (1, 128, 2112, 32), (1, 64, 1100, 64)])
+def test_attention_last_strip_as_a_launch_of_its_own(B, H, N, d):
+    x = wl.fused_inputs("t", "bf16", B, H, N, d, seed=2000 + H + N + d, row_factor=(0.5, 2.0))
+    V = wl.value_inputs(x, seed=2001 + N)
+    O = gu.to_f64(_run(x, V))
+    assert np.isfinite(O).all()
+    first_tail = N // 256 * 256 if N % 256 <= 64 else N - 8
+    for hh in sorted({0, H // 2, H - 1}):
+        _check_rows(O[0, hh], x, V, 0, hh, [(0, 40), (first_tail - 20, N)], f"attention {B}x{H}x{N}x{d} head {hh}")
+
+
 def test_attention_any_length_scale_zero_is_the_column_mean():
     x = wl.fused_inputs("t", "bf16", 1, 1, 333, 64, seed=21, scale=0.0)
     V = wl.value_inputs(x, seed=22)
