@@ -275,3 +275,13 @@ def test_many_short_sequences_in_a_captured_graph(what):
         fn = attnw.attnw_fused if what == "fused" else attnw.attnw_gemm_scores
         P = torch.empty((B, H, N, N), dtype=torch.bfloat16, device="cuda")
         _captured_replays_match_eager(lambda s: fn(Q, K, P, B, H, N, d, sc, attnw.ATTNW_BF16, s), P)
+
+
+def test_attention_with_a_launch_for_the_last_strip_in_a_captured_graph():
+    """Two launches per call (the full strips, then the last few queries with their keys spread over four waves)."""
+    B, H, N, d = 1, 64, 1025, 64
+    x = wl.fused_inputs("t", "bf16", B, H, N, d, seed=2600)
+    Q, K = gu.to_dev(x.Q, "bf16"), gu.to_dev(x.K, "bf16")
+    V = gu.to_dev(wl.value_inputs(x, seed=2601), "bf16")
+    O = torch.empty((B, H, N, d), dtype=torch.bfloat16, device="cuda")
+    _captured_replays_match_eager(lambda s: attnw.attnw_attention(Q, K, V, O, B, H, N, d, float(x.scale), attnw.ATTNW_BF16, s), O)
