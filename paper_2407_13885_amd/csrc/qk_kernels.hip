@@ -824,14 +824,17 @@ hipError_t launch_qk(DType dt, bool scores_only, const void* Q, const void* K, v
     // N = 64, d = 32 69 / 35 -> 10 / 10; 1024 heads of d = 64: N = 33 14 / 11 -> 6 / 5.5, 64 20 / 12 -> 6 / 6, 100 22 / 17 -> 16 / 15,
     // 128 25 / 17 -> 18 / 17; 16 heads: N = 49, d = 32 8.9 / 6.3 -> 4.3 / 4.2, N = 127, d = 96 12.6 / 9.3 -> 6.8 / 6.1.  Not taken:
     // N = 128 with fewer than 512 (head, 32 queries) pairs (64 heads of d = 64: 5.4 / 3.8 against 5.7 / 5.1), scores of
-    // lengths that are multiples of 32 with fewer than 2048 pairs (256 heads of N = 128: 5.4 against 6.0).
+    // lengths that are multiples of 32 with few pairs (256 heads of N = 128: 5.4 against 6.0; 192 heads of N = 128, d = 64:
+    // 5.2 against 5.6; N = 64, d = 32, 384 pairs: 4.6 against 4.8 -- taken from 1024 pairs on, from 384 up to 96 tokens, and
+    // for every head size above 64, whose rows the kernels below pad: 1536 heads of N = 32, d = 64 16.3 -> 4.7 us, 768
+    // heads of N = 64, d = 64 9.2 -> 5.6, 384 heads of N = 128, d = 64 8.7 -> 7.8, 192 heads of N = 96, d = 128 12.5 -> 6.6).
     if (qk_tiny_supported(BH, N, d)) {
         const int64_t units = BH * ((N + 31) / 32);
         // 128 < N <= 256 (d <= 64; the operands of the next unit are requested later in a unit, two waves per SIMD), 1024 heads,
         // fused / scores against the kernels below: N = 129, d = 64 27 / 23 against 35 / 29; 160 30 / 25 against 45 / 25; 192
         // 38 / 33 against 49 / 27; 197 48 / 43 against 52 / 41; 223 50 / 47 against 51 / 43; 224 51 / 44 against 55 / 32; d = 32:
         // N = 144 12 / 12 against 22 / 19, 197 28 / 27 against 42 / 30, 256 31 / 28 against 42 / 27 (4096 heads: 159 / 157 against 141 / 96)
-        const bool take = N <= 128 ? (scores_only ? ((N % 32) != 0 || units >= 2048) : !(N == 128 && units < 512))
+        const bool take = N <= 128 ? (scores_only ? ((N % 32) != 0 || units >= 1024 || (N <= 96 && units >= 384) || d > 64) : !(N == 128 && units < 512))
                                    : (scores_only ? ((N % 32) != 0 && (N <= 160 || (d <= 32 && (N & 1) && N <= 224)))
                                                   : (N <= 192 || ((d <= 32 || (N & 1)) && N <= 224)));
         if (tiny || (!force && take)) return launch_qk_tiny(scores_only, Q, K, out, BH, N, d, scale, stream);
