@@ -374,6 +374,7 @@ SHAPES_ATTENTION = [("bf16", 1, 16, 4096, 128), ("bf16", 1, 16, 4096, 64), ("bf1
                     ("bf16", 1, 1, 1024, 128), ("bf16", 1, 1, 4096, 128), ("bf16", 1, 4, 4096, 128), ("bf16", 1, 1, 16384, 128),
                     ("bf16", 1, 1, 4096, 64), ("bf16", 1, 16, 4096, 96), ("bf16", 1, 16, 4096, 256), ("bf16", 1, 16, 4096, 192),
                     ("bf16", 4096, 3, 49, 32), ("bf16", 1024, 4, 64, 32), ("bf16", 256, 16, 49, 64), ("bf16", 64, 12, 128, 64),
+                    ("bf16", 4, 16, 2049, 64), ("bf16", 8, 16, 1025, 64), ("bf16", 16, 12, 577, 64), ("bf16", 1, 16, 4097, 128),
                     ("f32", 1, 16, 4096, 128), ("f32", 1, 16, 4096, 64), ("f32", 1, 16, 4096, 256), ("f32", 8, 16, 512, 64)]
 
 
