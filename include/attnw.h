@@ -58,6 +58,14 @@
  *       gang     the gang kernel wherever it takes the shape
  *       tiny     the wave-per-head kernel wherever it takes the shape
  *     Weights of all of them agree to rounding of the row sum, scores bit for bit.
+ *     The workgroups of the gang kernel wait for each other's row statistics
+ *     inside one launch, so all of a gang must be running at once: the grid is
+ *     what the chip holds and a gang is a run of consecutive workgroups, which a
+ *     device that starts workgroups in order completes whatever runs beside the
+ *     call.  Every wait is bounded all the same: should other work keep a member
+ *     off the chip for some tenths of a second, the rows that wait for it come
+ *     out as NaN instead of the device hanging.  ATTNW_FUSED_KERNEL=rounds keeps
+ *     a process that shares the device with long-running kernels off it.
  */
 #ifndef ATTNW_H
 #define ATTNW_H
