@@ -179,3 +179,45 @@ def test_fused_beyond_the_round_kernel_lengths(N):
     gu.check_weights(got, ref, "bf16", f"N = {N} sampled rows")
     mean_rel = ((got - ref) / np.maximum(ref, 1e-300)).mean(-1)
     assert float(np.abs(mean_rel).max()) <= 6e-5, f"mean signed relative error of a row {np.abs(mean_rel).max():.2e}"
+
+
+def _bits(t):
+    """bf16 device tensor -> host array of its bit patterns (the oracle's storage type)."""
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def test_more_than_two_to_the_31_elements_of_short_sequences_and_rows():
+    """600000 windows of 64 tokens (2.46e9 weights, 4.9 GB) and 5e7 softmax rows of 49 columns (2.45e9 elements):
+    element indices beyond 32 bits in the kernels that pack many heads / rows into a wave.  Inputs are drawn on the
+    device (seeded); every row sum on the device, the first, middle and last heads / row blocks against the oracle."""
+    import paper_2407_13885_amd as attnw
+    torch.manual_seed(77)
+    BH, N, d = 600000, 64, 32
+    Q = torch.randn(1, BH, N, d, device="cuda", dtype=torch.bfloat16)
+    K = torch.randn_like(Q)
+    P = torch.empty(1, BH, N, N, device="cuda", dtype=torch.bfloat16)
+    scale = d ** -0.5
+    attnw.attnw_fused(Q, K, P, 1, BH, N, d, scale, attnw.ATTNW_BF16)
+    torch.cuda.synchronize()
+    flat = P.view(-1, N)
+    step = 1 << 22
+    worst = max(float((flat[i:i + step].float().sum(-1) - 1).abs().max().item()) for i in range(0, flat.shape[0], step))
+    assert worst <= gu.ROWSUM_BF16, f"row sum off by {worst:.3e}"
+    for h in (0, 1, BH // 2, 524288, 524289, BH - 2, BH - 1):      # (524288 * 64 * 64 = 2^31 elements)
+        ref = oracle.attention_weights(_bits(Q[0, h]), _bits(K[0, h]), "bf16", np.float32(scale))
+        gu.check_weights(gu.to_f64(P[0, h]), ref, "bf16", f"head {h} of {BH}")
+    del P, Q, K, flat
+    torch.cuda.empty_cache()
+
+    rows, cols = 50_000_000, 49
+    S = torch.empty(rows, cols, device="cuda", dtype=torch.bfloat16)
+    for i in range(0, rows, step):
+        S[i:i + step] = (torch.randn(min(step, rows - i), cols, device="cuda") * 2).to(torch.bfloat16)
+    W = torch.empty_like(S)
+    attnw.attnw_softmax(S, W, rows, cols, attnw.ATTNW_BF16)
+    torch.cuda.synchronize()
+    worst = max(float((W[i:i + step].float().sum(-1) - 1).abs().max().item()) for i in range(0, rows, step))
+    assert worst <= gu.ROWSUM_BF16, f"softmax row sum off by {worst:.3e}"
+    for r0 in (0, rows // 2, 43826196 - 500, rows - 1000):         # (43826196 * 49 crosses 2^31 elements)
+        ref = oracle.softmax(_bits(S[r0:r0 + 1000]), "bf16")
+        gu.check_weights(gu.to_f64(W[r0:r0 + 1000]), ref, "bf16", f"softmax rows {r0}..")
