@@ -324,6 +324,20 @@ def test_softmax_in_place(dtype, cols):
     gu.check_weights(gu.to_f64(P), oracle.softmax(s.S, dtype), dtype, f"in-place {dtype} cols={cols}")
 
 
+# Rows off the 16-byte boundaries that share a wave: the chunk two rows of a block share leaves as one store, put
+# together in LDS behind a barrier that every load of the block precedes -- in place, a row count that leaves the last
+# block partly empty, 16 and 32 lanes per row.
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("cols", [67, 197, 393, 251])
+def test_softmax_in_place_rows_that_share_chunks_within_a_block(dtype, cols):
+    rows = 1003
+    s = wl.softmax_inputs("t", dtype, rows, cols, seed=520 + cols, sigma=2.0, peak_fraction=0.02)
+    S = gu.to_dev(s.S, dtype)
+    P = gu.run_softmax(S, rows, cols, dtype, inplace=True)
+    assert P.data_ptr() == S.data_ptr()
+    gu.check_weights(gu.to_f64(P), oracle.softmax(s.S, dtype), dtype, f"in-place {dtype} {rows} x {cols}")
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("cols", [7, 100, 1001, 2048, 2049, 70000, 300001])
 def test_softmax_rows_of_the_lowest_finite_value(dtype, cols):
