@@ -366,6 +366,10 @@ void qk_kernel(const T* __restrict__ Q, const T* __restrict__ K, T* __restrict__
     // exponentials (Eq. 1), kept per lane; kbase = first key of this lane's first run
     auto fold_stats = [&](f32x16 (&acc)[QB], int kbase, auto tailc) {
         constexpr bool tail = decltype(tailc)::value != 0;   // this tile holds keys past N
+        if constexpr (tail) {
+            // (wave-uniform: lane 0's kbase is the sub-tile's first key) a sub-tile wholly past N adds nothing
+            if (__builtin_amdgcn_readfirstlane(kbase) >= N) return;
+        }
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
             if constexpr (tail) {
